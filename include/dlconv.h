@@ -1,0 +1,121 @@
+/*
+ * dlconv.h -- C boundary of the MI355X (gfx950) convolution + loss library.
+ *
+ * One GPU's per-step work of the paper's DeepLabv3+-style segmentation
+ * network: dense 2-D convolution with stride, zero padding and dilation
+ * (forward, data gradient, filter gradient) on NHWC fp16/bf16 tensors with
+ * fp32 accumulation, and the class-weighted per-pixel softmax cross-entropy
+ * for the 3-class mask.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, densely
+ *     packed, base address 16-byte aligned.  Descriptor pointers are HOST
+ *     pointers.  The library allocates nothing, keeps no state and never
+ *     synchronises: work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns at once.
+ *   - Outputs are fully overwritten (never accumulated into).
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation returns an error code and touches no device memory.
+ *   - Activations are NHWC, filters KRSC (output channel, filter row, filter
+ *     column, input channel).  Convolution is cross-correlation (no filter
+ *     flip), one group, no bias.
+ *   - Results are deterministic run to run (no floating-point atomics).
+ */
+#ifndef DLCONV_H
+#define DLCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DL_OK = 0,
+    DL_ERR_NULL = 1,         /* a required pointer is NULL                        */
+    DL_ERR_SHAPE = 2,        /* non-positive extent, empty output, size overflow  */
+    DL_ERR_DTYPE = 3,        /* dtype outside what the entry point accepts        */
+    DL_ERR_ALIGN = 4,        /* a tensor base is not 16-byte aligned              */
+    DL_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the query says     */
+    DL_ERR_UNSUPPORTED = 6,  /* valid request the kernels cannot serve            */
+    DL_ERR_LAUNCH = 7        /* the HIP runtime refused a launch                  */
+} dl_status;
+
+typedef enum { DL_F16 = 0, DL_BF16 = 1, DL_F32 = 2 } dl_dtype;
+
+enum { DL_PASS_FWD = 0, DL_PASS_BWD_DATA = 1, DL_PASS_BWD_FILTER = 2 };
+
+/* Geometry of one convolution, in the paper's naming of a convolution's
+ * dimensions (Sec. "Performance Measurement": filter R x S, image H x W,
+ * C input channels, K output channels, batch N).  Plain data, caller-owned. */
+typedef struct {
+    int32_t N, H, W, C;                 /* input  x : [N, H, W, C]                 */
+    int32_t K, R, S;                    /* filter w : [K, R, S, C]                 */
+    int32_t stride_h, stride_w;         /* >= 1                                    */
+    int32_t pad_h, pad_w;               /* >= 0, zeros on both sides of each axis  */
+    int32_t dil_h, dil_w;               /* >= 1, atrous sampling step              */
+    int32_t dtype;                      /* dl_dtype of x, w, y, dy, dx: F16 | BF16 */
+    int32_t dw_dtype;                   /* dl_dtype of dw: same as dtype, or F32   */
+} dl_conv_desc;
+
+/* Output extent  P = floor((H + 2*pad_h - dil_h*(R-1) - 1) / stride_h) + 1,
+ * Q likewise along W.  DL_ERR_SHAPE if the descriptor is invalid or P, Q < 1. */
+dl_status dl_conv_out_shape(const dl_conv_desc *desc, int32_t *P, int32_t *Q);
+
+/* Bytes of device scratch the given pass (DL_PASS_*) needs; may be 0. */
+dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *bytes);
+
+/* Forward convolution, incl. atrous convolution with a dilation factor
+ * (paper, Sec. "Segmentation Architecture"):
+ *   y[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r*dil_h,
+ *                               q*stride_w - pad_w + s*dil_w, c] * w[k,r,s,c],
+ * out-of-image terms are zero.  x: [N,H,W,C], w: [K,R,S,C], y: [N,P,Q,K],
+ * all `dtype`; products are accumulated in fp32 and rounded once (nearest
+ * even) on store. */
+dl_status conv2d_fwd(const dl_conv_desc *desc, const void *x, const void *w, void *y,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Data gradient (paper, Sec. "Deep learning ...": each layer is
+ * differentiable; backward convolutions in the kernel breakdown): the adjoint
+ * of conv2d_fwd with respect to x applied to dy.
+ *   dx[n,h,w,c] = sum over (p,r),(q,s),k with p*stride_h - pad_h + r*dil_h == h
+ *                 and q*stride_w - pad_w + s*dil_w == w of dy[n,p,q,k]*w[k,r,s,c].
+ * dy: [N,P,Q,K], w: [K,R,S,C], dx: [N,H,W,C].  Every element of dx is
+ * written, including those no output pixel reaches (zeros). */
+dl_status conv2d_bwd_data(const dl_conv_desc *desc, const void *dy, const void *w, void *dx,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Filter gradient:
+ *   dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r*dil_h,
+ *                                             q*stride_w - pad_w + s*dil_w, c].
+ * x: [N,H,W,C], dy: [N,P,Q,K], dw: [K,R,S,C] in `dw_dtype`.  The reduction
+ * over N*P*Q is split across workgroups into fp32 partials held in the
+ * workspace and summed in a fixed order. */
+dl_status conv2d_bwd_filter(const dl_conv_desc *desc, const void *x, const void *dy, void *dw,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Scratch bytes for weighted_pixel_ce_fwd_bwd on n_pixels pixels. */
+dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes);
+
+/* Class-weighted per-pixel softmax cross-entropy over 3 classes (paper,
+ * Sec. "Weighted loss": each pixel's loss is scaled by the weight of its
+ * labelled class), value and gradient in one pass:
+ *   l_i  = -log softmax(z_i)[label_i]
+ *   loss = scale * sum_i class_weights[label_i] * l_i
+ *   dlogits_i[c] = scale * class_weights[label_i] * (softmax(z_i)[c] - [c == label_i])
+ * logits, dlogits: [n_pixels, 3] in `dtype` (F16 | BF16); labels: [n_pixels]
+ * uint8 in {0,1,2} (other values: undefined result, no fault); class_weights:
+ * device float[3]; loss: device float[1].  Math is fp32 with the row maximum
+ * subtracted.  n_pixels == 0 writes loss = 0. */
+dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,
+                                    const float *class_weights, float scale, int64_t n_pixels,
+                                    float *loss, void *dlogits,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+const char *dl_status_string(dl_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLCONV_H */

@@ -172,7 +172,8 @@ void oracle_conv_fwd_at(const oracle_conv_desc *d, const float *x, const float *
 }
 
 /* dx[n,h,w,c] gathers every (p, r) pair with p*st - pad + r*dil == h (and the
- * same along w): the same set of terms the scatter form adds into it. */
+ * same along w): the same set of terms the scatter form adds into it.  For a
+ * given tap r the matching p, if any, is (h + pad - r*dil) / st. */
 void oracle_conv_bwd_data_at(const oracle_conv_desc *d, const float *dy, const float *w,
                              const int64_t *idx, int64_t n_idx, double *out)
 {
@@ -186,16 +187,18 @@ void oracle_conv_bwd_data_at(const oracle_conv_desc *d, const float *dy, const f
         int h  = (int)(t % d->H); t /= d->H;
         int n  = (int)t;
         double acc = 0.0;
-        for (int p = 0; p < P; ++p)
-            for (int r = 0; r < d->R; ++r) {
-                if (p * d->stride_h - d->pad_h + r * d->dil_h != h) continue;
-                for (int q = 0; q < Q; ++q)
-                    for (int s = 0; s < d->S; ++s) {
-                        if (q * d->stride_w - d->pad_w + s * d->dil_w != ww) continue;
-                        for (int k = 0; k < d->K; ++k)
-                            acc += (double)dy[YI(n, p, q, k)] * (double)w[WI(k, r, s, c)];
-                    }
+        for (int r = 0; r < d->R; ++r) {
+            int th = h + d->pad_h - r * d->dil_h;
+            if (th < 0 || th % d->stride_h != 0 || th / d->stride_h >= P) continue;
+            int p = th / d->stride_h;
+            for (int s = 0; s < d->S; ++s) {
+                int tw = ww + d->pad_w - s * d->dil_w;
+                if (tw < 0 || tw % d->stride_w != 0 || tw / d->stride_w >= Q) continue;
+                int q = tw / d->stride_w;
+                for (int k = 0; k < d->K; ++k)
+                    acc += (double)dy[YI(n, p, q, k)] * (double)w[WI(k, r, s, c)];
             }
+        }
         out[i] = acc;
     }
 }

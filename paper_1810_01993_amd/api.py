@@ -1,0 +1,219 @@
+"""Thin Python binding of ``libdlconv.so`` (see ``include/dlconv.h``).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels behind the C boundary.  torch is used to own device memory and to
+name the current HIP stream.  There is no CPU fallback: if the library has
+not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdlconv.so")
+
+DL_F16, DL_BF16, DL_F32 = 0, 1, 2
+PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
+
+EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data",
+           "conv2d_bwd_filter", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "dl_status_string")
+
+
+class DlError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {_lib.dl_status_string(code).decode()} (status {code})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
+                 "dil_h", "dil_w", "dtype", "dw_dtype")]
+
+
+@dataclass(frozen=True)
+class ConvDesc:
+    """Mirror of ``dl_conv_desc``."""
+    N: int
+    H: int
+    W: int
+    C: int
+    K: int
+    R: int
+    S: int
+    stride_h: int = 1
+    stride_w: int = 1
+    pad_h: int = 0
+    pad_w: int = 0
+    dil_h: int = 1
+    dil_w: int = 1
+    dtype: int = DL_F16
+    dw_dtype: int | None = None
+
+    def c_struct(self) -> _Desc:
+        dwt = self.dtype if self.dw_dtype is None else self.dw_dtype
+        return _Desc(self.N, self.H, self.W, self.C, self.K, self.R, self.S, self.stride_h, self.stride_w,
+                     self.pad_h, self.pad_w, self.dil_h, self.dil_w, self.dtype, dwt)
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1810_01993_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    dp = ctypes.POINTER(_Desc)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    lib.dl_conv_out_shape.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.dl_conv_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(sz)]
+    for name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_filter"):
+        getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
+    lib.weighted_pixel_ce_fwd_bwd.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64,
+                                              vp, vp, vp, sz, vp]
+    for name in EXPORTS:
+        getattr(lib, name).restype = ctypes.c_int
+    lib.dl_status_string.argtypes = [ctypes.c_int]
+    lib.dl_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise DlError(code, where)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return DL_F16
+    if t.dtype == torch.bfloat16:
+        return DL_BF16
+    raise TypeError(f"fp16 or bf16 tensor required, got {t.dtype}")
+
+
+def _dev_ptr(t: torch.Tensor | None) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("contiguous device tensor required")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def dl_conv_out_shape(desc: ConvDesc):
+    P, Q = ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.dl_conv_out_shape(ctypes.byref(desc.c_struct()), ctypes.byref(P), ctypes.byref(Q)), "dl_conv_out_shape")
+    return P.value, Q.value
+
+
+def dl_conv_workspace_bytes(desc: ConvDesc, which: int) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.dl_conv_workspace_bytes(ctypes.byref(desc.c_struct()), which, ctypes.byref(n)), "dl_conv_workspace_bytes")
+    return n.value
+
+
+def dl_ce_workspace_bytes(n_pixels: int) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.dl_ce_workspace_bytes(n_pixels, ctypes.byref(n)), "dl_ce_workspace_bytes")
+    return n.value
+
+
+def _workspace(nbytes: int, device, workspace: torch.Tensor | None):
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def _expect(t: torch.Tensor, shape, name: str):
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def conv2d_fwd(desc: ConvDesc, x: torch.Tensor, w: torch.Tensor, y: torch.Tensor | None = None,
+               workspace: torch.Tensor | None = None) -> torch.Tensor:
+    P, Q = dl_conv_out_shape(desc)
+    _expect(x, (desc.N, desc.H, desc.W, desc.C), "x")
+    _expect(w, (desc.K, desc.R, desc.S, desc.C), "w")
+    if _dtype_code(x) != desc.dtype or w.dtype != x.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    if y is None:
+        y = torch.empty((desc.N, P, Q, desc.K), dtype=x.dtype, device=x.device)
+    _expect(y, (desc.N, P, Q, desc.K), "y")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_FWD), x.device, workspace)
+    _check(_lib.conv2d_fwd(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(w), _dev_ptr(y), _dev_ptr(ws), nb,
+                           _stream()), "conv2d_fwd")
+    return y
+
+
+def conv2d_bwd_data(desc: ConvDesc, dy: torch.Tensor, w: torch.Tensor, dx: torch.Tensor | None = None,
+                    workspace: torch.Tensor | None = None) -> torch.Tensor:
+    P, Q = dl_conv_out_shape(desc)
+    _expect(dy, (desc.N, P, Q, desc.K), "dy")
+    _expect(w, (desc.K, desc.R, desc.S, desc.C), "w")
+    if _dtype_code(dy) != desc.dtype or w.dtype != dy.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    if dx is None:
+        dx = torch.empty((desc.N, desc.H, desc.W, desc.C), dtype=dy.dtype, device=dy.device)
+    _expect(dx, (desc.N, desc.H, desc.W, desc.C), "dx")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_BWD_DATA), dy.device, workspace)
+    _check(_lib.conv2d_bwd_data(ctypes.byref(desc.c_struct()), _dev_ptr(dy), _dev_ptr(w), _dev_ptr(dx), _dev_ptr(ws),
+                                nb, _stream()), "conv2d_bwd_data")
+    return dx
+
+
+def conv2d_bwd_filter(desc: ConvDesc, x: torch.Tensor, dy: torch.Tensor, dw: torch.Tensor | None = None,
+                      workspace: torch.Tensor | None = None) -> torch.Tensor:
+    P, Q = dl_conv_out_shape(desc)
+    _expect(x, (desc.N, desc.H, desc.W, desc.C), "x")
+    _expect(dy, (desc.N, P, Q, desc.K), "dy")
+    if _dtype_code(x) != desc.dtype or dy.dtype != x.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    dwt = desc.dtype if desc.dw_dtype is None else desc.dw_dtype
+    if dw is None:
+        dw = torch.empty((desc.K, desc.R, desc.S, desc.C), device=x.device,
+                         dtype=torch.float32 if dwt == DL_F32 else x.dtype)
+    _expect(dw, (desc.K, desc.R, desc.S, desc.C), "dw")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_BWD_FILTER), x.device, workspace)
+    _check(_lib.conv2d_bwd_filter(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(dy), _dev_ptr(dw),
+                                  _dev_ptr(ws), nb, _stream()), "conv2d_bwd_filter")
+    return dw
+
+
+def weighted_pixel_ce_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,
+                              scale: float, loss: torch.Tensor | None = None,
+                              dlogits: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """logits [..., 3] fp16/bf16, labels [...] uint8, class_weights float32[3]
+    (device).  Returns (loss: float32[1] device tensor, dlogits)."""
+    if logits.shape[-1] != 3:
+        raise ValueError("3 classes expected in the last dimension")
+    n = labels.numel()
+    if logits.numel() != 3 * n or labels.dtype != torch.uint8:
+        raise ValueError("labels must be uint8 with one entry per pixel")
+    if class_weights.dtype != torch.float32 or class_weights.numel() != 3:
+        raise ValueError("class_weights must be float32[3]")
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=logits.device)
+    if dlogits is None:
+        dlogits = torch.empty_like(logits)
+    ws, nb = _workspace(dl_ce_workspace_bytes(n), logits.device, workspace)
+    _check(_lib.weighted_pixel_ce_fwd_bwd(_dev_ptr(logits), _dtype_code(logits), _dev_ptr(labels),
+                                          _dev_ptr(class_weights), ctypes.c_float(scale), n, _dev_ptr(loss),
+                                          _dev_ptr(dlogits), _dev_ptr(ws), nb, _stream()),
+           "weighted_pixel_ce_fwd_bwd")
+    return loss, dlogits
+
+
+def desc_from_layer(layer, dtype: str, dw_f32: bool = False) -> ConvDesc:
+    """ConvDesc for a ``layers.ConvLayer`` ('f16' | 'bf16')."""
+    code = {"f16": DL_F16, "bf16": DL_BF16}[dtype]
+    return ConvDesc(layer.N, layer.H, layer.W, layer.C, layer.K, layer.R, layer.S, layer.stride, layer.stride,
+                    layer.pad, layer.pad, layer.dil, layer.dil, code, DL_F32 if dw_f32 else code)

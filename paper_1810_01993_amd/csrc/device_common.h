@@ -1,0 +1,97 @@
+// Device-side building blocks shared by the gfx950 kernels: 16-bit storage
+// types, fp32 -> fp16/bf16 rounding, and the 32x32x16 MFMA tile product read
+// out of LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dlk {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+// Storage-type traits.  Tensors are handled as raw 16-bit patterns; only the
+// MFMA instruction and the final rounding differ between the two types.
+struct F16 {
+    static __device__ __forceinline__ floatx16_t mfma(u32x4_t a, u32x4_t b, floatx16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
+        return __builtin_bit_cast(uint16_t, (_Float16)f);
+    }
+    static __device__ __forceinline__ float to_float(uint16_t h) {
+        return (float)__builtin_bit_cast(_Float16, h);
+    }
+};
+
+struct BF16 {
+    static __device__ __forceinline__ floatx16_t mfma(u32x4_t a, u32x4_t b, floatx16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
+        uint32_t u = __builtin_bit_cast(uint32_t, f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // quiet NaN
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+    static __device__ __forceinline__ float to_float(uint16_t h) {
+        return __builtin_bit_cast(float, (uint32_t)h << 16);
+    }
+};
+
+// LDS tiles are [rows][BK] 16-bit elements with BK = 32 and the row pitch
+// padded to 40 elements (80 bytes): the 16-byte fragment reads of 8
+// consecutive rows then fall into 8 different 16-byte bank groups.
+constexpr int BK = 32;
+constexpr int LDS_PITCH = BK + 8;
+
+// One BK-deep step of the block tile product.  The wave owns TM x TN MFMA
+// tiles of 32x32; sa / sb point at the wave's first row in the current LDS
+// buffers.  Operand layout of v_mfma_f32_32x32x16: lane l supplies row
+// (l % 32), reduction elements 8*(l / 32) .. +7 of each 16-deep slice.
+template <class T, int TM, int TN>
+__device__ __forceinline__ void mma_step(const uint16_t *sa, const uint16_t *sb, int lane,
+                                         floatx16_t (&acc)[TM][TN])
+{
+    const int frag = (lane & 31) * LDS_PITCH + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+        u32x4_t a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            a[i] = *reinterpret_cast<const u32x4_t *>(sa + i * 32 * LDS_PITCH + frag + ks * 16);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            b[j] = *reinterpret_cast<const u32x4_t *>(sb + j * 32 * LDS_PITCH + frag + ks * 16);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = T::mfma(a[i], b[j], acc[i][j]);
+    }
+}
+
+// Accumulator layout of a 32x32 MFMA tile: register v of lane l holds
+// row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+__device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// Spread consecutive workgroup ids over the 8 XCDs so that each XCD (own L2)
+// works through one contiguous run of tiles.  Workgroups are dealt to XCDs
+// round-robin by id; this maps id -> tile so that XCD x gets tiles
+// [x*n/8, (x+1)*n/8).
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks)
+{
+    constexpr int XCDS = 8;
+    const int per = nblocks / XCDS, rem = nblocks % XCDS;
+    const int xcd = bid % XCDS, slot = bid / XCDS;
+    // XCDs [0, rem) own per+1 tiles, the rest own per tiles
+    const int start = xcd * per + (xcd < rem ? xcd : rem);
+    return start + slot;
+}
+
+}  // namespace dlk

@@ -1,0 +1,71 @@
+// Host-visible launch interface of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dlk {
+
+// Implicit-GEMM convolution engine: D[m, j] = sum_{t, c} A[pixel(m, t), c] * B[j, t, c].
+//   m indexes (n, oh, ow) of an output grid [N, OH, OW]; t = (jr, js) a grid of
+//   TR x TS taps; the input pixel of tap t is
+//       ih = oh*sh + th0 + jr*dth,   iw = ow*sw + tw0 + js*dtw,
+//   outside [0,IH) x [0,IW) it contributes zero.  B is [Nout][TR*TS*Cin],
+//   reduction index contiguous.  Row m is stored at
+//       D + (((n*FH) + oh*osh + ooh)*FW + ow*osw + oow)*ldd.
+// The forward pass uses it directly; the data gradient uses it once per
+// stride-parity class of the input pixels with a re-laid-out filter.
+struct IgemmArgs {
+    const uint16_t *A;
+    const uint16_t *B;
+    uint16_t *D;
+    int32_t NB;                 // batch
+    int32_t IH, IW, Cin;        // A extents
+    int32_t OH, OW;             // output grid of this launch
+    int32_t Nout;               // GEMM N
+    int32_t TR, TS;             // tap grid
+    int32_t sh, sw;
+    int32_t th0, dth, tw0, dtw;
+    int32_t FH, FW, osh, osw, ooh, oow, ldd;
+};
+
+// is_bf16 selects the MFMA flavour and the output rounding.
+hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+
+// Filter re-layout for the data gradient: for one stride-parity class,
+//   wt[c][jr][js][k] = w[k][r0 + jr*rstep][s0 + js*sstep][c]
+struct FilterRelayoutArgs {
+    const uint16_t *w;          // [K][R][S][C]
+    uint16_t *wt;               // [C][TR][TS][K]
+    int32_t K, R, S, C;
+    int32_t r0, rstep, TR, s0, sstep, TS;
+};
+hipError_t launch_filter_relayout(const FilterRelayoutArgs &a, hipStream_t stream);
+
+// Filter gradient: partial[z][k][j] = sum over the z-th slice of the N*P*Q
+// pixels of dy[pix][k] * x[pixel(pix, tap(j)), c(j)],  j = (r*S + s)*C + c.
+struct WgradArgs {
+    const uint16_t *x;          // [N,H,W,C]
+    const uint16_t *dy;         // [N,P,Q,K]
+    float *partial;             // [splits][K][R*S*C]
+    int32_t N, H, W, C, K, R, S, P, Q;
+    int32_t sh, sw, ph, pw, dh, dw;
+    int32_t splits;             // slices of the pixel range
+    int32_t chunk;              // pixels per slice, multiple of 32
+};
+hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream);
+
+// dw[i] = sum_z partial[z][i] in ascending z, rounded to out_dtype (dl_dtype).
+hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
+                                hipStream_t stream);
+
+// Weighted per-pixel cross-entropy, 3 classes.
+int ce_num_blocks(int64_t n_pixels);
+hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *cw,
+                              float scale, int64_t n_pixels, float *loss, uint16_t *dlogits, float *partials,
+                              hipStream_t stream);
+
+// Heuristic shared by the workspace query and the launch.
+int wgrad_pick_splits(int64_t npix, int K, int RSC);
+
+}  // namespace dlk

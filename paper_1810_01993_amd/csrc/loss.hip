@@ -1,0 +1,129 @@
+// Class-weighted per-pixel softmax cross-entropy over 3 classes, value and
+// gradient in one streaming pass (13 bytes of traffic per pixel: 6 logits in,
+// 1 label in, 6 gradient out).
+//
+// A thread handles 8 consecutive pixels per trip: three 16-byte loads cover
+// their 24 logits, one 8-byte load their labels, three 16-byte stores the
+// gradient.  The weighted losses are summed per thread, reduced across the
+// wavefront with lane shuffles and across the workgroup through LDS; each
+// workgroup writes one fp32 partial and a one-workgroup second kernel adds
+// the partials in a fixed order, so the result is deterministic.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dlk {
+
+constexpr int CE_THREADS = 256;
+constexpr int CE_MAX_BLOCKS = 2048;
+
+int ce_num_blocks(int64_t n_pixels)
+{
+    const int64_t groups = (n_pixels + 7) / 8;
+    int64_t b = (groups + CE_THREADS - 1) / CE_THREADS;
+    if (b > CE_MAX_BLOCKS) b = CE_MAX_BLOCKS;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+// One pixel: returns w * (logsumexp - z_label) and overwrites z0..z2 with the gradient.
+__device__ __forceinline__ float ce_pixel(float &z0, float &z1, float &z2, int lab, float w0, float w1, float w2,
+                                          float scale)
+{
+    const float m = fmaxf(z0, fmaxf(z1, z2));
+    const float e0 = __expf(z0 - m), e1 = __expf(z1 - m), e2 = __expf(z2 - m);
+    const float se = e0 + e1 + e2;
+    const float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
+    const float w = lab == 0 ? w0 : (lab == 1 ? w1 : w2);
+    const float l = w * (m + __logf(se) - zl);
+    const float g = scale * w / se;
+    z0 = g * e0 - (lab == 0 ? scale * w : 0.f);
+    z1 = g * e1 - (lab == 1 ? scale * w : 0.f);
+    z2 = g * e2 - (lab == 2 ? scale * w : 0.f);
+    return l;
+}
+
+template <class T>
+__global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restrict__ logits,
+                                                        const uint8_t *__restrict__ labels,
+                                                        const float *__restrict__ cw, float scale, int64_t n,
+                                                        uint16_t *__restrict__ dlogits, float *__restrict__ partials)
+{
+    const float w0 = cw[0], w1 = cw[1], w2 = cw[2];
+    float sum = 0.f;
+    const int64_t full_groups = n / 8;
+    const int64_t stride = (int64_t)gridDim.x * CE_THREADS;
+    for (int64_t g = (int64_t)blockIdx.x * CE_THREADS + threadIdx.x; g < full_groups; g += stride) {
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(logits + g * 24);
+        u32x4_t v[3] = {src[0], src[1], src[2]};
+        const u32x2_t lb = *reinterpret_cast<const u32x2_t *>(labels + g * 8);
+        float z[24];
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            const uint32_t u = v[i >> 2][i & 3];
+            z[2 * i] = T::to_float((uint16_t)(u & 0xffffu));
+            z[2 * i + 1] = T::to_float((uint16_t)(u >> 16));
+        }
+#pragma unroll
+        for (int px = 0; px < 8; ++px) {
+            const int lab = (lb[px >> 2] >> (8 * (px & 3))) & 0xff;
+            sum += ce_pixel(z[3 * px], z[3 * px + 1], z[3 * px + 2], lab, w0, w1, w2, scale);
+        }
+#pragma unroll
+        for (int i = 0; i < 12; ++i)
+            v[i >> 2][i & 3] = (uint32_t)T::from_float(z[2 * i]) | ((uint32_t)T::from_float(z[2 * i + 1]) << 16);
+        u32x4_t *dst = reinterpret_cast<u32x4_t *>(dlogits + g * 24);
+        dst[0] = v[0];
+        dst[1] = v[1];
+        dst[2] = v[2];
+    }
+    // ragged tail (< 8 pixels): one thread each
+    if (blockIdx.x == 0) {
+        const int64_t i = full_groups * 8 + threadIdx.x;
+        if (threadIdx.x < 8 && i < n) {
+            float z0 = T::to_float(logits[i * 3]), z1 = T::to_float(logits[i * 3 + 1]), z2 = T::to_float(logits[i * 3 + 2]);
+            sum += ce_pixel(z0, z1, z2, labels[i], w0, w1, w2, scale);
+            dlogits[i * 3] = T::from_float(z0);
+            dlogits[i * 3 + 1] = T::from_float(z1);
+            dlogits[i * 3 + 2] = T::from_float(z2);
+        }
+    }
+    // wavefront reduction, then across the 4 wavefronts through LDS
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    __shared__ float wsum[CE_THREADS / 64];
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+__global__ __launch_bounds__(CE_THREADS) void ce_finish_kernel(const float *__restrict__ partials, int n_partials,
+                                                               float scale, float *__restrict__ loss)
+{
+    float sum = 0.f;
+    for (int i = threadIdx.x; i < n_partials; i += CE_THREADS) sum += partials[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    __shared__ float wsum[CE_THREADS / 64];
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) loss[0] = scale * ((wsum[0] + wsum[1]) + (wsum[2] + wsum[3]));
+}
+
+hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *cw,
+                              float scale, int64_t n_pixels, float *loss, uint16_t *dlogits, float *partials,
+                              hipStream_t stream)
+{
+    const int blocks = ce_num_blocks(n_pixels);
+    if (is_bf16)
+        hipLaunchKernelGGL(ce_kernel<BF16>, dim3(blocks), dim3(CE_THREADS), 0, stream, logits, labels, cw, scale,
+                           n_pixels, dlogits, partials);
+    else
+        hipLaunchKernelGGL(ce_kernel<F16>, dim3(blocks), dim3(CE_THREADS), 0, stream, logits, labels, cw, scale,
+                           n_pixels, dlogits, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, blocks, scale, loss);
+    return hipGetLastError();
+}
+
+}  // namespace dlk

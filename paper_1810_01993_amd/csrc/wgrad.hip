@@ -1,0 +1,269 @@
+// Filter-gradient kernel for gfx950.
+//
+// GEMM view: rows = output channel k, columns j = (r*S + s)*C + c, reduction
+// over the N*P*Q output pixels.  Both operands are stored channel-contiguous
+// (NHWC) while the MFMA wants 8 consecutive reduction elements (pixels) per
+// lane, so tiles are transposed on their way into LDS: a thread loads the
+// same 8 channels of 4 consecutive pixels, regroups them in registers into
+// 8 x (4 pixels) and writes 8-byte pieces into a [channel][pixel] LDS tile.
+// The pixel range is cut into `splits` slices (grid.y); every slice writes an
+// fp32 partial tile, and a second kernel adds the slices in a fixed order.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dlk {
+
+struct PixelCursor {          // (n, p, q) of one output pixel, advanced without division
+    int n, p, q;
+    __device__ __forceinline__ void init(int pix, int P, int Q) {
+        n = pix / (P * Q);
+        const int rem = pix - n * (P * Q);
+        p = rem / Q;
+        q = rem - p * Q;
+    }
+    __device__ __forceinline__ void advance(int by, int P, int Q) {
+        q += by;
+        while (q >= Q) {
+            q -= Q;
+            if (++p == P) { p = 0; ++n; }
+        }
+    }
+};
+
+template <class T, int BM, int BN, int WM, int WN, bool VECA, bool VECB>
+__global__ __launch_bounds__(WM *WN * 64) void wgrad_kernel(const WgradArgs p)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int PG = 4;                              // pixels regrouped per thread item
+    constexpr int ITEMS_A = (BM / 8) * (BK / PG), ITEMS_B = (BN / 8) * (BK / PG);
+    constexpr int IA = (ITEMS_A + NT - 1) / NT, IB = (ITEMS_B + NT - 1) / NT;
+
+    extern __shared__ __align__(16) uint16_t lds[];
+    uint16_t *sA = lds;                                // [2][BM][LDS_PITCH]   dy^T : [k][pixel]
+    uint16_t *sB = lds + 2 * BM * LDS_PITCH;           // [2][BN][LDS_PITCH]   x^T  : [j][pixel]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int RSC = p.R * p.S * p.C;
+    const int npix = p.N * p.P * p.Q;
+    const int tiles_n = (RSC + BN - 1) / BN;
+    const int k0 = (blockIdx.x / tiles_n) * BM, j0 = (blockIdx.x % tiles_n) * BN;
+    const int pix_begin = blockIdx.y * p.chunk;
+    const int pix_end = min(npix, pix_begin + p.chunk);
+
+    // ---- item coordinates --------------------------------------------------
+    // item -> (cv = 8-channel column group, pg = group of 4 consecutive pixels)
+    int b_ih[IB], b_iw[IB], b_c[IB];                   // tap offset and channel of the item's columns
+    bool b_col_ok[IB];
+    PixelCursor cur[IB];
+#pragma unroll
+    for (int it = 0; it < IB; ++it) {
+        const int item = tid + it * NT;
+        const int cv = item % (BN / 8), pg = item / (BN / 8);
+        const int j = j0 + cv * 8;
+        b_col_ok[it] = item < ITEMS_B && j < RSC;
+        const int tap = j / p.C;
+        b_c[it] = j - tap * p.C;
+        const int r = tap / p.S, s = tap - r * p.S;
+        b_ih[it] = r * p.dh - p.ph;
+        b_iw[it] = s * p.dw - p.pw;
+        cur[it].init(pix_begin + pg * PG, p.P, p.Q);
+    }
+
+    u32x4_t ra[IA][PG], rb[IB][PG];
+    int pix_base = pix_begin;                          // first pixel of the block being loaded
+
+    auto load_tiles = [&]() {
+#pragma unroll
+        for (int it = 0; it < IA; ++it) {
+            const int item = tid + it * NT;
+            const int cv = item % (BM / 8), pg = item / (BM / 8);
+            const int k = k0 + cv * 8;
+#pragma unroll
+            for (int g = 0; g < PG; ++g) {
+                const int pix = pix_base + pg * PG + g;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (item < ITEMS_A && pix < pix_end) {
+                    if constexpr (VECA) {
+                        if (k < p.K) v = *reinterpret_cast<const u32x4_t *>(p.dy + (size_t)pix * p.K + k);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const uint32_t h = (k + e < p.K) ? p.dy[(size_t)pix * p.K + k + e] : 0u;
+                            v[e >> 1] |= h << (16 * (e & 1));
+                        }
+                    }
+                }
+                ra[it][g] = v;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IB; ++it) {
+            const int item = tid + it * NT;
+            const int pg = item / (BN / 8);
+            PixelCursor pc = cur[it];
+#pragma unroll
+            for (int g = 0; g < PG; ++g) {
+                const int pix = pix_base + pg * PG + g;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (b_col_ok[it] && pix < pix_end) {
+                    if constexpr (VECB) {
+                        const int ih = pc.p * p.sh + b_ih[it], iw = pc.q * p.sw + b_iw[it];
+                        if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
+                            v = *reinterpret_cast<const u32x4_t *>(
+                                p.x + (size_t)((pc.n * p.H + ih) * p.W + iw) * p.C + b_c[it]);
+                    } else {
+                        const int cv = item % (BN / 8);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int j = j0 + cv * 8 + e;
+                            uint32_t h = 0u;
+                            if (j < RSC) {
+                                const int tap = j / p.C, c = j - tap * p.C;
+                                const int r = tap / p.S, s = tap - r * p.S;
+                                const int ih = pc.p * p.sh - p.ph + r * p.dh, iw = pc.q * p.sw - p.pw + s * p.dw;
+                                if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
+                                    h = p.x[(size_t)((pc.n * p.H + ih) * p.W + iw) * p.C + c];
+                            }
+                            v[e >> 1] |= h << (16 * (e & 1));
+                        }
+                    }
+                }
+                rb[it][g] = v;
+                pc.advance(1, p.P, p.Q);
+            }
+            cur[it].advance(BK, p.P, p.Q);
+        }
+        pix_base += BK;
+    };
+
+    // [4 pixels][8 channels] -> [8 channels][4 pixels], 8-byte LDS writes
+    auto store_transposed = [&](uint16_t *dst_tile, const u32x4_t (&r)[PG], int cv, int pg) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            u32x2_t lo, hi;                             // channel 2d and channel 2d+1
+            lo[0] = (r[0][d] & 0xffffu) | (r[1][d] << 16);
+            lo[1] = (r[2][d] & 0xffffu) | (r[3][d] << 16);
+            hi[0] = (r[0][d] >> 16) | (r[1][d] & 0xffff0000u);
+            hi[1] = (r[2][d] >> 16) | (r[3][d] & 0xffff0000u);
+            *reinterpret_cast<u32x2_t *>(dst_tile + (cv * 8 + 2 * d) * LDS_PITCH + pg * PG) = lo;
+            *reinterpret_cast<u32x2_t *>(dst_tile + (cv * 8 + 2 * d + 1) * LDS_PITCH + pg * PG) = hi;
+        }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < IA; ++it) {
+            const int item = tid + it * NT;
+            if (item < ITEMS_A) store_transposed(sA + buf * BM * LDS_PITCH, ra[it], item % (BM / 8), item / (BM / 8));
+        }
+#pragma unroll
+        for (int it = 0; it < IB; ++it) {
+            const int item = tid + it * NT;
+            if (item < ITEMS_B) store_transposed(sB + buf * BN * LDS_PITCH, rb[it], item % (BN / 8), item / (BN / 8));
+        }
+    };
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = pix_end > pix_begin ? (pix_end - pix_begin + BK - 1) / BK : 0;
+    if (nk > 0) {
+        load_tiles();
+        store_tiles(0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cb = kt & 1;
+            if (kt + 1 < nk) load_tiles();
+            mma_step<T, TM, TN>(sA + cb * BM * LDS_PITCH + wm * TM * 32 * LDS_PITCH,
+                                sB + cb * BN * LDS_PITCH + wn * TN * 32 * LDS_PITCH, lane, acc);
+            if (kt + 1 < nk) store_tiles(cb ^ 1);
+            __syncthreads();
+        }
+    }
+
+    float *out = p.partial + (size_t)blockIdx.y * p.K * RSC;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + (wm * TM + i) * 32 + acc_row(v, lane);
+            if (k >= p.K) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = j0 + (wn * TN + j) * 32 + (lane & 31);
+                if (col < RSC) out[(size_t)k * RSC + col] = acc[i][j][v];
+            }
+        }
+}
+
+int wgrad_pick_splits(int64_t npix, int K, int RSC)
+{
+    // Enough workgroups to fill 256 CUs about four times over, at least 64
+    // pixels per slice, never more than 256 slices.
+    const int64_t tiles = (int64_t)((K + 127) / 128) * ((RSC + 127) / 128);
+    int64_t s = (1024 + tiles - 1) / tiles;
+    const int64_t max_by_len = (npix + 63) / 64;
+    if (s > max_by_len) s = max_by_len;
+    if (s > 256) s = 256;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+template <class T, int BM, int BN, int WM, int WN>
+static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
+{
+    const int RSC = a.R * a.S * a.C;
+    const int64_t tiles = (int64_t)((a.K + BM - 1) / BM) * ((RSC + BN - 1) / BN);
+    constexpr size_t lds = size_t(2) * (BM + BN) * LDS_PITCH * sizeof(uint16_t);
+    static_assert(lds <= 64 * 1024, "needs the dynamic LDS attribute");
+    const dim3 grid((unsigned)tiles, (unsigned)a.splits), block(WM * WN * 64);
+    const bool va = a.K % 8 == 0, vb = a.C % 8 == 0;
+    if (va && vb)
+        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, true, true>), grid, block, lds, stream, a);
+    else if (vb)
+        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, false, true>), grid, block, lds, stream, a);
+    else if (va)
+        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, true, false>), grid, block, lds, stream, a);
+    else
+        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, false, false>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
+{
+    return is_bf16 ? launch_cfg<BF16, 128, 128, 2, 2>(a, stream) : launch_cfg<F16, 128, 128, 2, 2>(a, stream);
+}
+
+// ---- ordered reduction of the split partials ------------------------------
+template <int OUT>   // 0 f16, 1 bf16, 2 f32
+__global__ void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n, void *out)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int z = 0; z < splits; ++z) s += partial[(size_t)z * n + i];
+        if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
+        else if constexpr (OUT == 1) reinterpret_cast<uint16_t *>(out)[i] = BF16::from_float(s);
+        else reinterpret_cast<float *>(out)[i] = s;
+    }
+}
+
+hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
+                                hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t want = (n + 255) / 256;
+    const dim3 grid((unsigned)(want < 8192 ? want : 8192)), block(256);
+    if (out_dtype == 0) hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out);
+    else if (out_dtype == 1) hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out);
+    else hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out);
+    return hipGetLastError();
+}
+
+}  // namespace dlk

@@ -119,25 +119,31 @@ def _paint_ellipse(mask, cy, cx, a, b, theta):
     mask[y0:y1, x0:x1] |= (u * u + v * v) <= 1.0
 
 
-def _fill_to_fraction(g, H, W, target_px, tol_px, axes, blocked=None):
-    """Paint random ellipses into a fresh mask until the count of painted,
-    unblocked pixels is within ``tol_px`` of ``target_px``."""
+def _fill_to_fraction(g, H, W, target_px, axes, blocked=None):
+    """Paint random ellipses into a fresh mask until exactly ``target_px``
+    unblocked pixels are painted: ellipses never larger than 80 % of what is
+    still missing, and single pixels for the last few."""
     mask = np.zeros((H, W), dtype=bool)
+    free = np.ones((H, W), dtype=bool) if blocked is None else ~blocked
 
-    def count():
-        return int((mask & ~blocked).sum()) if blocked is not None else int(mask.sum())
-
-    for _ in range(10000):
-        missing = target_px - count()
-        if missing <= tol_px // 2:
+    for _ in range(100000):
+        missing = target_px - int((mask & free).sum())
+        if missing <= 0:
+            break
+        if missing < 12:
+            cand = np.flatnonzero((~mask & free).ravel())
+            mask.ravel()[g.choice(cand, size=missing, replace=False)] = True
             break
         (a_lo, a_hi), (b_lo, b_hi) = axes
         a, b = g.uniform(a_lo, a_hi), g.uniform(b_lo, b_hi)
         area = np.pi * a * b
-        if area > missing:                       # last patch: shrink to what is left
-            f = np.sqrt(missing / area)
-            a, b = max(a * f, 1.0), max(b * f, 1.0)
-        _paint_ellipse(mask, g.uniform(0, H), g.uniform(0, W), a, b, g.uniform(0, np.pi))
+        if area > 0.8 * missing:                 # late patches shrink to what is left
+            f = np.sqrt(0.8 * missing / area)
+            a, b = max(a * f, 0.6), max(b * f, 0.6)
+        trial = mask.copy()
+        _paint_ellipse(trial, g.uniform(0, H), g.uniform(0, W), a, b, g.uniform(0, np.pi))
+        if int((trial & free).sum()) <= target_px:
+            mask = trial
     return mask
 
 
@@ -151,9 +157,9 @@ def ellipse_labels(seed: int, N: int, H: int, W: int, freq=CLASS_FREQ, tol: floa
     npx = H * W
     scale = np.sqrt(npx / (768.0 * 1152.0))     # ellipse sizes follow the grid size
     for n in range(N):
-        tc = _fill_to_fraction(g, H, W, round(freq[2] * npx), int(tol * npx),
+        tc = _fill_to_fraction(g, H, W, round(freq[2] * npx),
                                ((6 * scale, 12 * scale), (5 * scale, 10 * scale)))
-        ar = _fill_to_fraction(g, H, W, round(freq[1] * npx), int(tol * npx),
+        ar = _fill_to_fraction(g, H, W, round(freq[1] * npx),
                                ((60 * scale, 200 * scale), (8 * scale, 25 * scale)), blocked=tc)
         out[n][ar] = 1
         out[n][tc] = 2

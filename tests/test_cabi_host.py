@@ -1,0 +1,79 @@
+"""Host-only checks of the C boundary: the library loads without a GPU,
+exports every symbol the header declares, and rejects bad arguments before
+touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1810_01993_amd import build
+    if not os.path.exists(build.LIB):
+        build.build_library()
+    from paper_1810_01993_amd import api as _api
+    return _api
+
+
+def test_every_declared_symbol_is_exported(api):
+    header = open(os.path.join(ROOT, "include", "dlconv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", header))
+    assert {"conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_filter", "weighted_pixel_ce_fwd_bwd"} <= declared
+    lib = ctypes.CDLL(api.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in dlconv.h but not exported"
+    assert declared == set(api.EXPORTS)
+
+
+def test_out_shape_and_workspace_queries(api):
+    d = api.ConvDesc(2, 768, 1152, 16, 64, 7, 7, 2, 2, 3, 3, 1, 1, api.DL_BF16)
+    assert api.dl_conv_out_shape(d) == (384, 576)
+    assert api.dl_conv_workspace_bytes(d, api.PASS_FWD) == 0
+    # data gradient: room for the re-laid-out filter (every tap lands in exactly one parity class)
+    assert api.dl_conv_workspace_bytes(d, api.PASS_BWD_DATA) >= 64 * 7 * 7 * 16 * 2
+    ws = api.dl_conv_workspace_bytes(d, api.PASS_BWD_FILTER)
+    assert ws >= 64 * 7 * 7 * 16 * 4 and ws % (64 * 7 * 7 * 16 * 4) == 0
+    assert api.dl_ce_workspace_bytes(0) >= 4
+    assert api.dl_ce_workspace_bytes(2 * 768 * 1152) >= 4
+
+
+def _code(fn, *a):
+    with pytest.raises(Exception) as e:
+        fn(*a)
+    return e.value.code
+
+
+def test_descriptor_validation(api):
+    ok = dict(N=1, H=8, W=8, C=8, K=8, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, dil_h=1, dil_w=1,
+              dtype=api.DL_F16)
+    assert api.dl_conv_out_shape(api.ConvDesc(**ok)) == (8, 8)
+    for field, bad in [("N", 0), ("C", -1), ("K", 0), ("R", 0), ("stride_h", 0), ("dil_w", 0), ("pad_h", -1)]:
+        assert _code(api.dl_conv_out_shape, api.ConvDesc(**{**ok, field: bad})) == 2, field
+    assert _code(api.dl_conv_out_shape, api.ConvDesc(**{**ok, "H": 2, "pad_h": 0, "dil_h": 2})) == 2   # empty output
+    assert _code(api.dl_conv_out_shape, api.ConvDesc(**{**ok, "dtype": api.DL_F32})) == 3
+    assert _code(api.dl_conv_out_shape, api.ConvDesc(**{**ok, "dtype": api.DL_F16, "dw_dtype": api.DL_BF16})) == 3
+    assert _code(api.dl_conv_out_shape, api.ConvDesc(**{**ok, "N": 4096, "H": 4096, "W": 4096})) == 2  # index overflow
+    assert _code(api.dl_conv_workspace_bytes, api.ConvDesc(**ok), 7) == 6
+
+
+def test_pointer_checks_happen_before_any_launch(api):
+    lib = api._lib
+    d = api.ConvDesc(1, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, api.DL_F16).c_struct()
+    ref = ctypes.byref(d)
+    for fn in (lib.conv2d_fwd, lib.conv2d_bwd_data, lib.conv2d_bwd_filter):
+        assert fn(ref, None, None, None, None, 0, None) == 1           # null
+        assert fn(None, 16, 16, 16, None, 0, None) == 1
+        assert fn(ref, 16, 16, 24, None, 0, None) == 4                 # misaligned
+    assert lib.conv2d_bwd_data(ref, 16, 16, 16, None, 0, None) == 5    # workspace missing
+    assert lib.conv2d_bwd_filter(ref, 16, 16, 16, 32, 8, None) == 5    # workspace too small
+    assert lib.weighted_pixel_ce_fwd_bwd(None, 0, None, None, 1.0, 8, None, None, None, 0, None) == 1
+    assert lib.weighted_pixel_ce_fwd_bwd(16, 2, 16, 16, 1.0, 8, 16, 16, 16, 64, None) == 3
+    assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, -1, 16, 16, 16, 64, None) == 2
+    assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 16, None, 0, None) == 5
+    assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 24, 16, 64, None) == 4
+    assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)

@@ -1,0 +1,86 @@
+"""GPU parity: weighted_pixel_ce_fwd_bwd through the C boundary against the oracle."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1810_01993_amd import synth
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+# fp32 evaluation of log-sum-exp and an fp32 tree sum over the pixels: the
+# relative error of the scalar is a few fp32 ulps times log2(n) -- 1e-5 leaves
+# an order of magnitude of room at 1.8 M pixels.
+LOSS_RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1810_01993_amd import api as _api
+    assert torch.cuda.is_available()
+    return _api
+
+
+def _run(api, n, dtype, seed, labels=None, sigma=1.0, scale=None):
+    print(f"[case] weighted_ce n={n} {dtype} seed={seed} sigma={sigma}", flush=True)
+    sys.stdout.flush()
+    z32, zb = synth.quantize(synth.normal(seed, (n, 3), sigma=sigma), dtype)
+    if labels is None:
+        labels = synth.rng(seed + 1).choice(3, size=n, p=synth.CLASS_FREQ).astype(np.uint8)
+    scale = (1.0 / max(n, 1)) if scale is None else scale
+    cw = np.asarray(synth.CLASS_WEIGHTS, dtype=np.float32)
+    loss, dz = api.weighted_pixel_ce_fwd_bwd(U.to_device(zb, dtype), torch.from_numpy(labels).cuda(),
+                                             torch.from_numpy(cw).cuda(), scale)
+    torch.cuda.synchronize()
+    ref_loss, ref_dz = oracle.weighted_ce(z32, labels, cw.astype(np.float64), float(np.float32(scale)))
+    got_loss = float(loss.item())
+    if n:
+        assert abs(got_loss - ref_loss) <= LOSS_RTOL * abs(ref_loss), (got_loss, ref_loss)
+        err = U.rel_err(U.to_host_f64(dz), ref_dz)
+        assert err <= U.TOL[dtype], f"dlogits max|err|/max|ref| = {err:.3e}"
+        # the gradient of the labelled class is negative, the others positive
+        g = U.to_host_f64(dz)
+        assert np.all(g[np.arange(n), labels] <= 0)
+    else:
+        assert got_loss == 0.0
+    return got_loss
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 9, 1000, 8 * 257 + 3, 8 * 256 * 9 + 5])
+def test_sizes_and_ragged_tails(api, n, dtype):
+    _run(api, n, dtype, synth.seed_for(0, 900 + n % 97))
+
+
+def test_large_logits(api):
+    _run(api, 4099, "f16", synth.seed_for(0, 950), sigma=40.0)
+    _run(api, 4099, "bf16", synth.seed_for(0, 951), sigma=300.0)
+
+
+def test_config5_full_mask(api):
+    """N=2 full-resolution logits with the ellipse label mask, 1/(N*H*W) scale."""
+    labels = synth.ellipse_labels(synth.seed_for(5, 990), 2, 768, 1152).ravel()
+    got = _run(api, labels.size, "f16", synth.seed_for(5, 991), labels=labels)
+    assert got > 0
+
+
+def test_determinism_and_redzones(api):
+    n = 8 * 300 + 5
+    _, zb = synth.quantize(synth.normal(3, (n, 3)), "f16")
+    labels = synth.rng(4).integers(0, 3, n).astype(np.uint8)
+    cw = torch.tensor(synth.CLASS_WEIGHTS, dtype=torch.float32, device="cuda")
+    z, lab = U.to_device(zb, "f16"), torch.from_numpy(labels).cuda()
+    guard = 64
+    res = []
+    for _ in range(2):
+        buf = torch.full((3 * n + 2 * guard,), 77.0, dtype=torch.float16, device="cuda")
+        dz = buf[guard:guard + 3 * n].view(n, 3)
+        loss, _ = api.weighted_pixel_ce_fwd_bwd(z, lab, cw, 0.5, dlogits=dz)
+        torch.cuda.synchronize()
+        assert torch.all(buf[:guard] == 77.0) and torch.all(buf[-guard:] == 77.0)
+        res.append((loss.clone(), dz.clone()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
