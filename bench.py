@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv + loss hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+forward, data gradient and filter gradient of all 63 convolution layers of the
+DeepLabv3+-style network at N=2, 1152x768x16 (fp16 storage, fp32 accumulate),
+plus the weighted pixel cross-entropy on the full-resolution 3-class logits.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--table]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense fp16/bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+# The dominant kernel: the implicit-GEMM engine in its widest tile, which the
+# two full-resolution decoder 3x3 layers (87 % of all FLOPs) run for their
+# forward and data-gradient passes.
+DOMINANT_LAYERS = ("dec.3x3.304-256", "dec.3x3.256-256")
+DOMINANT_PASSES = ("fwd", "dgrad")
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "dominant_kernel_traffic.txt"))
+    return ap.parse_args()
+
+
+def device_inputs(layer, dtype, seed, torch):
+    """Synthetic tensors of the layer's shapes, generated on the device:
+    |N(0,1)| activations (post-ReLU-like), He-scaled filters, N(0,1) upstream
+    gradients; the stem gets smooth normalised fields from the host generator."""
+    from paper_1810_01993_amd import synth
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    xs = (layer.N, layer.H, layer.W, layer.C)
+    if layer.name == "stem7x7":
+        _, bits = synth.quantize(synth.smooth_fields(seed, *xs), "f16")
+        x = torch.from_numpy(bits.view(np.int16)).view(torch.float16).cuda()
+    else:
+        x = torch.randn(xs, generator=g, device="cuda", dtype=torch.float32).abs_().to(dtype)
+    sigma = float(np.sqrt(2.0 / (layer.R * layer.S * layer.C)))
+    w = (torch.randn((layer.K, layer.R, layer.S, layer.C), generator=g, device="cuda") * sigma).to(dtype)
+    dy = torch.randn((layer.N, layer.P, layer.Q, layer.K), generator=g, device="cuda", dtype=torch.float32).to(dtype)
+    return x, w, dy
+
+
+class LayerState:
+    """Device buffers of one occurrence of one layer shape."""
+
+    def __init__(self, api, layer, seed, torch):
+        self.layer = layer
+        self.desc = api.desc_from_layer(layer, "f16")
+        self.x, self.w, self.dy = device_inputs(layer, torch.float16, seed, torch)
+        self.y = torch.empty_like(self.dy)
+        self.dx = torch.empty_like(self.x)
+        self.dw = torch.empty_like(self.w)
+        nb = max(api.dl_conv_workspace_bytes(self.desc, p) for p in (0, 1, 2))
+        self.ws = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
+
+
+def cpu_baseline():
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload:
+    forward + data gradient + filter gradient of a 24-row slab of one image of
+    the 3x3 256->256 full-resolution decoder layer."""
+    import oracle
+    rows = 24
+    s = oracle.ConvShape(1, rows, 1152, 256, 256, 3, 3, 1, 1, 1)
+    g = np.random.default_rng(0)
+    x = np.abs(g.standard_normal((1, rows, 1152, 256)))
+    w = g.standard_normal((256, 3, 3, 256)) * np.sqrt(2.0 / 2304)
+    dy = g.standard_normal((1, rows, 1152, 256))
+    t0 = time.perf_counter()
+    oracle.conv_fwd(s, x, w)
+    oracle.conv_bwd_data(s, dy, w)
+    oracle.conv_bwd_filter(s, x, dy)
+    dt = time.perf_counter() - t0
+    flops = 3 * 2 * rows * 1152 * 256 * 256 * 9
+    cores = len(os.sched_getaffinity(0))
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"fwd+dgrad+wgrad of a {rows}x1152 slab (1 image) of dec.3x3.256-256, fp64, {dt:.1f} s"}
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel, from the committed
+    rocprofv3 counter summary (a 'bytes_per_launch = <number>' line)."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.strip().startswith("bytes_per_launch"):
+                    return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU's share of the step; it runs with --gpus 1 only "
+              "(no collectives are part of this build).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1810_01993_amd import api, layers, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    _, table = layers.config5()
+
+    # one buffer set per occurrence, so repeated shapes do not re-use cache-resident tensors
+    net = []
+    for li, layer in enumerate(table):
+        for occ in range(layer.count):
+            net.append(LayerState(api, layer, synth.seed_for(5, 100 * li + occ), torch))
+    n_pix = 2 * 768 * 1152
+    logits = torch.randn((n_pix, 3), device="cuda").to(torch.float16)
+    labels = torch.from_numpy(synth.ellipse_labels(synth.seed_for(5, 990), 2, 768, 1152).ravel()).cuda()
+    cw = torch.tensor(synth.CLASS_WEIGHTS, dtype=torch.float32, device="cuda")
+    dlogits = torch.empty_like(logits)
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    ce_ws = torch.empty(max(api.dl_ce_workspace_bytes(n_pix), 16), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        def rec(key):
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                events.append((key, e))
+        for i, st in enumerate(net):
+            rec((i, "fwd", 0))
+            api.conv2d_fwd(st.desc, st.x, st.w, y=st.y, workspace=st.ws)
+            rec((i, "fwd", 1))
+        rec(("loss", "loss", 0))
+        api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n_pix, loss=loss, dlogits=dlogits, workspace=ce_ws)
+        rec(("loss", "loss", 1))
+        for i in range(len(net) - 1, -1, -1):
+            st = net[i]
+            rec((i, "dgrad", 0))
+            api.conv2d_bwd_data(st.desc, st.dy, st.w, dx=st.dx, workspace=st.ws)
+            rec((i, "dgrad", 1))
+            rec((i, "wgrad", 0))
+            api.conv2d_bwd_filter(st.desc, st.x, st.dy, dw=st.dw, workspace=st.ws)
+            rec((i, "wgrad", 1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = []
+        step(ev)
+        all_events.append(ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # per-call device times from the HIP events recorded inside the timed region
+    times = {}
+    for ev in all_events:
+        opened = {}
+        for (key, e) in ev:
+            who, which, end = key
+            if end == 0:
+                opened[(who, which)] = e
+            else:
+                times.setdefault((who, which), []).append(opened[(who, which)].elapsed_time(e))
+    med = {k: float(np.median(v)) for k, v in times.items()}
+
+    step_flops = layers.total_flops(table, passes=3)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    dom_ms, dom_flops, dom_n = 0.0, 0.0, 0
+    for i, st in enumerate(net):
+        if st.layer.name in DOMINANT_LAYERS:
+            for which in DOMINANT_PASSES:
+                dom_ms += float(np.mean(times[(i, which)]))
+                dom_flops += st.layer.flops()
+                dom_n += 1
+    achieved = (dom_flops / dom_n) / (dom_ms / dom_n * 1e-3) / 1e12
+    conv_ms = sum(v for (who, which), v in med.items() if which != "loss")
+    loss_ms = med[("loss", "loss")]
+
+    if args.table:
+        print(f"{'layer':28s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%peak':>6s} {'GB/s(min)':>10s}", file=sys.stderr)
+        for i, st in enumerate(net):
+            for which in ("fwd", "dgrad", "wgrad"):
+                ms = med[(i, which)]
+                tf = st.layer.flops() / (ms * 1e-3) / 1e12
+                gbs = st.layer.bytes_fwd() / (ms * 1e-3) / 1e9
+                print(f"{st.layer.name:28s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f}",
+                      file=sys.stderr)
+        print(f"loss: {loss_ms:.4f} ms  ({13 * n_pix / (loss_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)", file=sys.stderr)
+        print(f"sum of per-call medians: conv {conv_ms:.3f} ms, loss {loss_ms:.4f} ms; wall {ms_per_step:.3f} ms/step",
+              file=sys.stderr)
+
+    out = {
+        "metric": "conv fwd+bwd TFLOP/s, DeepLabv3+ layers @1152x768x16 (63 conv layers x fwd/dgrad/wgrad + weighted pixel CE)",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, fp16 in / fp32 accumulate",
+                   "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
+                   "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
+                   "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": read_traffic(args.traffic_file),
+                     "kernel": "igemm_kernel (widest tile): fwd+dgrad of the two full-resolution decoder 3x3 layers",
+                     "launches_per_step": dom_n // args.steps if args.steps else 0,
+                     "avg_launch_ms": dom_ms / dom_n, "flop_per_launch": dom_flops / dom_n},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
