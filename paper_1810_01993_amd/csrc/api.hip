@@ -8,7 +8,7 @@
 
 namespace {
 
-constexpr int64_t MAX_ELEMS = (int64_t)1 << 31;     // kernels index tensors with 32-bit element offsets
+constexpr int64_t MAX_ELEMS = 0x7FF00000;     // 32-bit byte offsets, with room above for the out-of-range marker
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -80,17 +80,14 @@ size_t dgrad_workspace(const dl_conv_desc *d)
     return total;
 }
 
-struct WgradPlan { int splits, chunk; size_t bytes; };
-
-WgradPlan wgrad_plan(const dl_conv_desc *d, const Geometry &g)
+dlk::WgradPlan wgrad_plan(const dl_conv_desc *d, const Geometry &g)
 {
-    const int64_t npix = (int64_t)d->N * g.P * g.Q;
-    const int RSC = d->R * d->S * d->C;
-    int splits = dlk::wgrad_pick_splits(npix, d->K, RSC);
-    int64_t chunk = (npix + splits - 1) / splits;
-    chunk = (chunk + 31) / 32 * 32;
-    splits = (int)((npix + chunk - 1) / chunk);
-    return WgradPlan{splits, (int)chunk, (size_t)splits * (size_t)g.w_elems * sizeof(float)};
+    return dlk::wgrad_make_plan((int64_t)d->N * g.P * g.Q, d->K, d->C, d->R * d->S * d->C);
+}
+
+size_t wgrad_workspace(const dl_conv_desc *d, const Geometry &g)
+{
+    return (size_t)wgrad_plan(d, g).splits * (size_t)g.w_elems * sizeof(float);
 }
 
 dl_status hip_status(hipError_t e) { return e == hipSuccess ? DL_OK : DL_ERR_LAUNCH; }
@@ -134,7 +131,7 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
     switch (pass) {
         case DL_PASS_FWD: *bytes = 0; return DL_OK;
         case DL_PASS_BWD_DATA: *bytes = dgrad_workspace(desc); return DL_OK;
-        case DL_PASS_BWD_FILTER: *bytes = wgrad_plan(desc, g).bytes; return DL_OK;
+        case DL_PASS_BWD_FILTER: *bytes = wgrad_workspace(desc, g); return DL_OK;
     }
     return DL_ERR_UNSUPPORTED;
 }
@@ -226,8 +223,8 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     const dl_status st = check_desc(d, &g);
     if (st != DL_OK) return st;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return DL_ERR_ALIGN;
-    const WgradPlan plan = wgrad_plan(d, g);
-    if (!workspace || workspace_bytes < plan.bytes) return DL_ERR_WORKSPACE;
+    const dlk::WgradPlan plan = wgrad_plan(d, g);
+    if (!workspace || workspace_bytes < wgrad_workspace(d, g)) return DL_ERR_WORKSPACE;
     if (!aligned16(workspace)) return DL_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
@@ -239,7 +236,8 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w; a.dh = d->dil_h; a.dw = d->dil_w;
     a.splits = plan.splits;
     a.chunk = plan.chunk;
-    hipError_t e = dlk::launch_wgrad(a, d->dtype == DL_BF16, stream);
+    hipError_t e = plan.cfg >= 0 ? dlk::launch_wgrad_dma(a, d->dtype == DL_BF16, plan.cfg, stream)
+                                 : dlk::launch_wgrad(a, d->dtype == DL_BF16, stream);
     if (e != hipSuccess) return DL_ERR_LAUNCH;
     e = dlk::launch_splitk_reduce(a.partial, plan.splits, g.w_elems, dw, d->dw_dtype, stream);
     return hip_status(e);

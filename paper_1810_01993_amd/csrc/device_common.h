@@ -44,36 +44,83 @@ struct BF16 {
     }
 };
 
-// LDS tiles are [rows][BK] 16-bit elements with BK = 32 and the row pitch
-// padded to 40 elements (80 bytes): the 16-byte fragment reads of 8
-// consecutive rows then fall into 8 different 16-byte bank groups.
+// LDS tiles are [rows][BKT] 16-bit elements (BKT = 32 or 64) with the row
+// pitch padded by 8 elements (16 bytes): pitch/16 is then odd, so the 16-byte
+// fragment reads of 8 consecutive rows fall into 8 different 16-byte bank groups.
 constexpr int BK = 32;
 constexpr int LDS_PITCH = BK + 8;
 
-// One BK-deep step of the block tile product.  The wave owns TM x TN MFMA
+// One BKT-deep step of the block tile product.  The wave owns TM x TN MFMA
 // tiles of 32x32; sa / sb point at the wave's first row in the current LDS
 // buffers.  Operand layout of v_mfma_f32_32x32x16: lane l supplies row
 // (l % 32), reduction elements 8*(l / 32) .. +7 of each 16-deep slice.
-template <class T, int TM, int TN>
+template <class T, int TM, int TN, int BKT = BK>
 __device__ __forceinline__ void mma_step(const uint16_t *sa, const uint16_t *sb, int lane,
                                          floatx16_t (&acc)[TM][TN])
 {
-    const int frag = (lane & 31) * LDS_PITCH + (lane >> 5) * 8;
+    constexpr int PITCH = BKT + 8;
+    const int frag = (lane & 31) * PITCH + (lane >> 5) * 8;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < BKT / 16; ++ks) {
         u32x4_t a[TM], b[TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            a[i] = *reinterpret_cast<const u32x4_t *>(sa + i * 32 * LDS_PITCH + frag + ks * 16);
+            a[i] = *reinterpret_cast<const u32x4_t *>(sa + i * 32 * PITCH + frag + ks * 16);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            b[j] = *reinterpret_cast<const u32x4_t *>(sb + j * 32 * LDS_PITCH + frag + ks * 16);
+            b[j] = *reinterpret_cast<const u32x4_t *>(sb + j * 32 * PITCH + frag + ks * 16);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = T::mfma(a[i], b[j], acc[i][j]);
     }
+}
+
+// Buffer resource over a dense tensor: loads whose byte offset lies at or
+// beyond `bytes` return zero instead of touching memory, which is how zero
+// padding and ragged tile edges are fetched without branches.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+constexpr uint32_t OOB_OFFSET = 0xFFFFFF00u;      // beyond any tensor the boundary accepts
+
+__device__ __forceinline__ u32x4_t buffer_load_16B(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+}
+
+typedef int32_t i32x4_t __attribute__((ext_vector_type(4)));
+
+// LDS byte address of a __shared__ object.
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const void *)p);
+}
+
+// One direct-to-LDS load: every lane fetches 16 bytes at `byte_off` of the
+// buffer `rsrc` (zero if out of range) and the wave deposits them at LDS
+// address lds_base + 16*lane.  Written as inline assembly so that the
+// compiler's wait-count insertion does not treat every later LDS read as
+// dependent on it; completion is awaited explicitly before the barrier.
+__device__ __forceinline__ void dma_load_16B(i32x4_t rsrc, uint32_t lds_base, uint32_t byte_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(byte_off), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ i32x4_t make_rsrc_words(const void *base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)(uintptr_t)base;
+    i32x4_t r;
+    r[0] = (int32_t)(uint32_t)a;
+    r[1] = (int32_t)((uint32_t)(a >> 32) & 0xffffu);     // stride 0: raw buffer
+    r[2] = (int32_t)bytes;
+    r[3] = 0x00020000;
+    return r;
 }
 
 // Accumulator layout of a 32x32 MFMA tile: register v of lane l holds

@@ -5,33 +5,38 @@
 // (tap, input channel).  The im2col matrix is never materialised: each
 // 16-byte load of 8 consecutive input channels computes its own source pixel
 // from (output pixel, tap), which is where stride, padding and dilation
-// enter.  Tiles are staged global -> registers -> LDS (two LDS buffers, one
-// barrier per 32-deep step) and multiplied with v_mfma_f32_32x32x16.
+// enter.  Padding pixels and ragged tile edges are fetched as out-of-range
+// buffer loads, which return zero without a branch.  Tiles are staged
+// global -> registers -> LDS: two register sets keep the loads two reduction
+// steps ahead of the MFMAs, two LDS buffers need one barrier per step.
+#include <cstdlib>
+#include <cstring>
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
 namespace dlk {
 
-template <int BM, int BN>
-constexpr size_t igemm_lds_bytes() { return size_t(2) * (BM + BN) * LDS_PITCH * sizeof(uint16_t); }
-
-// VEC: Cin % 8 == 0, so every 8-element slice of the reduction index stays
-// inside one tap and is one aligned 16-byte load.  Otherwise elements are
-// fetched one by one.
-template <class T, int BM, int BN, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmArgs p)
+// ===========================================================================
+// Vector kernel: Cin % 8 == 0, so every 8-element slice of the reduction index
+// stays inside one tap and is one aligned 16-byte load.
+// ===========================================================================
+template <class T, int BM, int BN, int BKT, int WM, int WN, int MIN_WAVES>
+__global__ __launch_bounds__(WM *WN * 64, MIN_WAVES) void igemm_vec_kernel(const IgemmArgs p)
 {
     constexpr int NT = WM * WN * 64;
+    constexpr int PITCH = BKT + 8;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int ROWS_PER_PASS = NT / 4;          // 4 vectors of 8 elements per 32-deep row
-    constexpr int PA = BM / ROWS_PER_PASS, PB = (BN + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
-    constexpr bool B_PARTIAL = BN % ROWS_PER_PASS != 0;   // narrow filter tile: only rows < BN exist
-    static_assert(BM % ROWS_PER_PASS == 0, "tile / thread-count mismatch");
-    static_assert(TM >= 1 && TN >= 1, "wave tile too small");
+    constexpr int VPR = BKT / 8;                         // 16-byte vectors per tile row
+    constexpr int RPP = NT / VPR;                        // tile rows covered by one pass of all threads
+    constexpr int PA = BM / RPP, PB = (BN + RPP - 1) / RPP;
+    constexpr bool B_PARTIAL = BN % RPP != 0;            // narrow filter tile: only rows < BN exist
+    static_assert(BM % RPP == 0 && TM >= 1 && TN >= 1, "tile / thread-count mismatch");
 
     extern __shared__ __align__(16) uint16_t lds[];
-    uint16_t *sA = lds;                                  // [2][BM][LDS_PITCH]
-    uint16_t *sB = lds + 2 * BM * LDS_PITCH;             // [2][BN][LDS_PITCH]
+    uint16_t *sA = lds;                                  // [2][BM][PITCH]
+    uint16_t *sB = lds + 2 * BM * PITCH;                 // [2][BN][PITCH]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -42,98 +47,71 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmArgs p)
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
+    const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
+    const __amdgpu_buffer_rsrc_t rsB = make_rsrc(p.B, (uint32_t)p.Nout * Kred * 2u);
+
     // ---- per-thread load coordinates: fixed rows, fixed 8-element column --
-    const int vec = tid & 3, row0 = tid >> 2;
-    int a_pix[PA], a_ih[PA], a_iw[PA];
+    const int vec = tid % VPR, row0 = tid / VPR;
+    int a_base[PA], a_ih[PA], a_iw[PA];                  // element offset of tap (0,0), its pixel coordinates
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
-        const int m = m0 + row0 + i * ROWS_PER_PASS;
+        const int m = m0 + row0 + i * RPP;
         if (m < M) {
             const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
             const int oh = rem / p.OW, ow = rem - oh * p.OW;
-            a_pix[i] = n * p.IH * p.IW;
             a_ih[i] = oh * p.sh + p.th0;
             a_iw[i] = ow * p.sw + p.tw0;
+            a_base[i] = ((n * p.IH + a_ih[i]) * p.IW + a_iw[i]) * p.Cin;
         } else {
-            a_pix[i] = 0;
+            a_base[i] = 0;
             a_ih[i] = -(1 << 28);                        // fails every bounds test
             a_iw[i] = 0;
         }
+    }
+    uint32_t b_off[PB];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+        const int j = n0 + row0 + i * RPP;
+        const bool ok = j < p.Nout && (!B_PARTIAL || row0 + i * RPP < BN);
+        b_off[i] = ok ? (uint32_t)j * (uint32_t)Kred * 2u : OOB_OFFSET;
     }
     // reduction index of this thread's slice: kk = (jr*TS + js)*Cin + c
     int kk = vec * 8;
     int c = kk % p.Cin, js = (kk / p.Cin) % p.TS, jr = (kk / p.Cin) / p.TS;
 
-    u32x4_t ra[PA], rb[PB];
-    auto load_tiles = [&]() {
-        if constexpr (VEC) {
-            const bool kin = kk < Kred;
-            const int dh = jr * p.dth, dw = js * p.dtw;
+    auto load_tiles = [&](u32x4_t (&ra)[PA], u32x4_t (&rb)[PB]) {
+        const bool kin = kk < Kred;
+        const int dh = jr * p.dth, dw = js * p.dtw;
+        const int tap_off = (dh * p.IW + dw) * p.Cin + c;
 #pragma unroll
-            for (int i = 0; i < PA; ++i) {
-                const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
-                const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (ok) v = *reinterpret_cast<const u32x4_t *>(p.A + (size_t)(a_pix[i] + ih * p.IW + iw) * p.Cin + c);
-                ra[i] = v;
-            }
-#pragma unroll
-            for (int i = 0; i < PB; ++i) {
-                const int j = n0 + row0 + i * ROWS_PER_PASS;
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (kin && j < p.Nout && (!B_PARTIAL || row0 + i * ROWS_PER_PASS < BN))
-                    v = *reinterpret_cast<const u32x4_t *>(p.B + (size_t)j * Kred + kk);
-                rb[i] = v;
-            }
-        } else {
-            uint16_t ea[PA][8], eb[PB][8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int k1 = kk + e;
-                const bool kin = k1 < Kred;
-                const int t = k1 / p.Cin, c1 = k1 - t * p.Cin;
-                const int r1 = t / p.TS, s1 = t - r1 * p.TS;
-#pragma unroll
-                for (int i = 0; i < PA; ++i) {
-                    const int ih = a_ih[i] + r1 * p.dth, iw = a_iw[i] + s1 * p.dtw;
-                    const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
-                    ea[i][e] = ok ? p.A[(size_t)(a_pix[i] + ih * p.IW + iw) * p.Cin + c1] : (uint16_t)0;
-                }
-#pragma unroll
-                for (int i = 0; i < PB; ++i) {
-                    const int j = n0 + row0 + i * ROWS_PER_PASS;
-                    const bool in_tile = !B_PARTIAL || row0 + i * ROWS_PER_PASS < BN;
-                    eb[i][e] = (kin && j < p.Nout && in_tile) ? p.B[(size_t)j * Kred + k1] : (uint16_t)0;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < PA; ++i)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) ra[i][d] = (uint32_t)ea[i][2 * d] | ((uint32_t)ea[i][2 * d + 1] << 16);
-#pragma unroll
-            for (int i = 0; i < PB; ++i)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) rb[i][d] = (uint32_t)eb[i][2 * d] | ((uint32_t)eb[i][2 * d + 1] << 16);
+        for (int i = 0; i < PA; ++i) {
+            const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+            const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+            ra[i] = buffer_load_16B(rsA, ok ? (uint32_t)(a_base[i] + tap_off) * 2u : OOB_OFFSET);
         }
-        // step this thread's slice to the next 32-deep block
-        kk += BK;
-        if constexpr (VEC) {
-            c += BK;
-            while (c >= p.Cin) {
-                c -= p.Cin;
-                if (++js == p.TS) { js = 0; ++jr; }
-            }
-        }
-    };
-    auto store_tiles = [&](int buf) {
-        uint16_t *da = sA + buf * BM * LDS_PITCH + row0 * LDS_PITCH + vec * 8;
-        uint16_t *db = sB + buf * BN * LDS_PITCH + row0 * LDS_PITCH + vec * 8;
-#pragma unroll
-        for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4_t *>(da + i * ROWS_PER_PASS * LDS_PITCH) = ra[i];
 #pragma unroll
         for (int i = 0; i < PB; ++i)
-            if (!B_PARTIAL || row0 + i * ROWS_PER_PASS < BN)
-                *reinterpret_cast<u32x4_t *>(db + i * ROWS_PER_PASS * LDS_PITCH) = rb[i];
+            rb[i] = buffer_load_16B(rsB, (kin && b_off[i] != OOB_OFFSET) ? b_off[i] + (uint32_t)kk * 2u : OOB_OFFSET);
+        // step this thread's slice to the next BKT-deep block
+        kk += BKT;
+        c += BKT;
+        while (c >= p.Cin) {
+            c -= p.Cin;
+            if (++js == p.TS) { js = 0; ++jr; }
+        }
+    };
+    auto store_tiles = [&](int buf, const u32x4_t (&ra)[PA], const u32x4_t (&rb)[PB]) {
+        uint16_t *da = sA + buf * BM * PITCH + row0 * PITCH + vec * 8;
+        uint16_t *db = sB + buf * BN * PITCH + row0 * PITCH + vec * 8;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4_t *>(da + i * RPP * PITCH) = ra[i];
+#pragma unroll
+        for (int i = 0; i < PB; ++i)
+            if (!B_PARTIAL || row0 + i * RPP < BN) *reinterpret_cast<u32x4_t *>(db + i * RPP * PITCH) = rb[i];
+    };
+    auto mma = [&](int buf, floatx16_t (&acc)[TM][TN]) {
+        mma_step<T, TM, TN, BKT>(sA + buf * BM * PITCH + wm * TM * 32 * PITCH,
+                                 sB + buf * BN * PITCH + wn * TN * 32 * PITCH, lane, acc);
     };
 
     floatx16_t acc[TM][TN];
@@ -144,17 +122,23 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = (Kred + BK - 1) / BK;
+    const int nk = (Kred + BKT - 1) / BKT;
     if (nk > 0) {
-        load_tiles();
-        store_tiles(0);
+        // register set 0 holds even steps, set 1 odd steps; LDS buffer = step & 1
+        u32x4_t ra0[PA], rb0[PB], ra1[PA], rb1[PB];
+        load_tiles(ra0, rb0);
+        if (nk > 1) load_tiles(ra1, rb1);
+        store_tiles(0, ra0, rb0);
         __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < nk) load_tiles();
-            mma_step<T, TM, TN>(sA + cur * BM * LDS_PITCH + wm * TM * 32 * LDS_PITCH,
-                                sB + cur * BN * LDS_PITCH + wn * TN * 32 * LDS_PITCH, lane, acc);
-            if (kt + 1 < nk) store_tiles(cur ^ 1);
+        for (int kt = 0; kt < nk; kt += 2) {
+            if (kt + 2 < nk) load_tiles(ra0, rb0);
+            mma(0, acc);
+            if (kt + 1 < nk) store_tiles(1, ra1, rb1);
+            __syncthreads();
+            if (kt + 1 >= nk) break;
+            if (kt + 3 < nk) load_tiles(ra1, rb1);
+            mma(1, acc);
+            if (kt + 2 < nk) store_tiles(0, ra0, rb0);
             __syncthreads();
         }
     }
@@ -184,11 +168,113 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmArgs p)
     }
 }
 
-template <class T, int BM, int BN, int WM, int WN, bool VEC>
-static hipError_t launch_cfg(const IgemmArgs &a, hipStream_t stream)
+// ===========================================================================
+// Scalar kernel: any channel count; elements are fetched one by one.  Used
+// only when Cin is not a multiple of 8 (e.g. the 3-channel logits gradient).
+// ===========================================================================
+template <class T>
+__global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
 {
-    auto kern = igemm_kernel<T, BM, BN, WM, WN, VEC>;
-    constexpr size_t lds = igemm_lds_bytes<BM, BN>();
+    constexpr int BM = 128, BN = 64, WN = 2, TM = 2, TN = 1, RPP = 64, PA = 2, PB = 1;
+    __shared__ __align__(16) uint16_t sA[BM * LDS_PITCH];
+    __shared__ __align__(16) uint16_t sB[BN * LDS_PITCH];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int M = p.NB * p.OH * p.OW;
+    const int Kred = p.TR * p.TS * p.Cin;
+    const int tiles_n = (p.Nout + BN - 1) / BN;
+    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+
+    const int vec = tid & 3, row0 = tid >> 2;
+    int a_pix[PA], a_ih[PA], a_iw[PA];
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+        const int m = m0 + row0 + i * RPP;
+        if (m < M) {
+            const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+            const int oh = rem / p.OW, ow = rem - oh * p.OW;
+            a_pix[i] = n * p.IH * p.IW;
+            a_ih[i] = oh * p.sh + p.th0;
+            a_iw[i] = ow * p.sw + p.tw0;
+        } else {
+            a_pix[i] = 0;
+            a_ih[i] = -(1 << 28);
+            a_iw[i] = 0;
+        }
+    }
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
+
+    const int nk = (Kred + BK - 1) / BK;
+    for (int kt = 0; kt < nk; ++kt) {
+        uint16_t ea[PA][8], eb[PB][8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k1 = kt * BK + vec * 8 + e;
+            const bool kin = k1 < Kred;
+            const int t = k1 / p.Cin, c1 = k1 - t * p.Cin;
+            const int r1 = t / p.TS, s1 = t - r1 * p.TS;
+#pragma unroll
+            for (int i = 0; i < PA; ++i) {
+                const int ih = a_ih[i] + r1 * p.dth, iw = a_iw[i] + s1 * p.dtw;
+                const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+                ea[i][e] = ok ? p.A[(size_t)(a_pix[i] + ih * p.IW + iw) * p.Cin + c1] : (uint16_t)0;
+            }
+            const int j = n0 + row0;
+            eb[0][e] = (kin && j < p.Nout) ? p.B[(size_t)j * Kred + k1] : (uint16_t)0;
+        }
+        __syncthreads();                                 // previous step's fragment reads are done
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            u32x4_t v;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) v[d] = (uint32_t)ea[i][2 * d] | ((uint32_t)ea[i][2 * d + 1] << 16);
+            *reinterpret_cast<u32x4_t *>(sA + (row0 + i * RPP) * LDS_PITCH + vec * 8) = v;
+        }
+        {
+            u32x4_t v;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) v[d] = (uint32_t)eb[0][2 * d] | ((uint32_t)eb[0][2 * d + 1] << 16);
+            *reinterpret_cast<u32x4_t *>(sB + row0 * LDS_PITCH + vec * 8) = v;
+        }
+        __syncthreads();
+        mma_step<T, TM, TN, BK>(sA + wm * TM * 32 * LDS_PITCH, sB + wn * TN * 32 * LDS_PITCH, lane, acc);
+    }
+
+    const bool dense = (p.osh == 1 && p.osw == 1 && p.FH == p.OH && p.FW == p.OW);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + (wm * TM + i) * 32 + acc_row(v, lane);
+            if (m >= M) continue;
+            size_t row_off;
+            if (dense) {
+                row_off = (size_t)m * p.ldd;
+            } else {
+                const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+                const int oh = rem / p.OW, ow = rem - oh * p.OW;
+                row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
+            }
+            const int col = n0 + wn * 32 + (lane & 31);
+            if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][0][v]);
+        }
+}
+
+// ===========================================================================
+// Host side: tile selection and launch
+// ===========================================================================
+template <class T, int BM, int BN, int BKT, int WM, int WN, int MIN_WAVES>
+static hipError_t launch_vec(const IgemmArgs &a, hipStream_t stream)
+{
+    auto kern = igemm_vec_kernel<T, BM, BN, BKT, WM, WN, MIN_WAVES>;
+    constexpr size_t lds = size_t(2) * (BM + BN) * (BKT + 8) * sizeof(uint16_t);
+    static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS");
     static bool attr_set = false;                       // raising the LDS limit is idempotent
     if (lds > 64 * 1024 && !attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -203,17 +289,70 @@ static hipError_t launch_cfg(const IgemmArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Tuning override: DLCONV_IGEMM_CFG=<n> forces tile configuration n for every
+// vector-path launch (used by the tile sweeps; unset in normal use).
+static int forced_cfg()
+{
+    static int v = [] {
+        const char *e = std::getenv("DLCONV_IGEMM_CFG");
+        return e ? std::atoi(e) : -1;
+    }();
+    return v;
+}
+
 template <class T>
 static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 {
     const int64_t M = (int64_t)a.NB * a.OH * a.OW;
-    if (a.Cin % 8 != 0) return launch_cfg<T, 128, 64, 2, 2, false>(a, stream);
-    if (a.Nout <= 32) return launch_cfg<T, 128, 32, 4, 1, true>(a, stream);
-    if (a.Nout <= 64) return launch_cfg<T, 128, 64, 2, 2, true>(a, stream);
-    // wide outputs: the 256-row tile once there are enough of them to fill 256 CUs
-    const int64_t big_tiles = ((M + 255) / 256) * ((a.Nout + 127) / 128);
-    if (big_tiles >= 512) return launch_cfg<T, 256, 128, 2, 2, true>(a, stream);
-    return launch_cfg<T, 128, 128, 2, 2, true>(a, stream);
+    if (a.Cin % 8 != 0) {
+        const int64_t tiles = ((M + 127) / 128) * ((a.Nout + 63) / 64);
+        if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(igemm_scalar_kernel<T>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
+    int cfg = forced_cfg();
+    if (cfg < 0) {
+        // Largest tile that still yields enough workgroups for 256 CUs; tiles
+        // wider than the output-channel count (rounded up to 64) are not considered.
+        const int nmax = (a.Nout + 63) / 64 * 64;
+        auto blocks = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((a.Nout + bn - 1) / bn); };
+        if (nmax <= 32 || a.Nout <= 32) cfg = 104;                     // 64 x 32
+        else if (nmax >= 256 && blocks(256, 256) >= 200) cfg = 100;    // 256 x 256
+        else if (nmax >= 128 && blocks(128, 128) >= 400) cfg = 102;    // 128 x 128
+        else if (blocks(128, 64) >= 200) cfg = 103;                    // 128 x 64
+        else cfg = 108;                                                // 64 x 64
+    }
+    if (cfg >= 100) {
+        IgemmArgs b = a;
+        static const int force_order = [] {
+            const char *e = std::getenv("DLCONV_C_OUTER");
+            return e ? std::atoi(e) : -1;
+        }();
+        // channel-major order needs the tap mask to fit 64 bits and no chunk that is mostly padding
+        const bool cm_ok = a.TR * a.TS <= 64;
+        b.c_outer = cm_ok && (force_order >= 0 ? force_order != 0 : (a.Cin % 32 == 0 || a.Cin >= 128));
+        // A ragged last column tile of the widest configuration (e.g. 304 = 256 + 48 output
+        // channels) would run mostly empty: give the remainder to a narrower tile instead.
+        const int rem = a.Nout % 256;
+        if (cfg == 100 && a.Nout > 256 && rem != 0 && rem <= 128) {
+            IgemmArgs lo = b, hi = b;
+            lo.Nout = a.Nout - rem;
+            hi.Nout = rem;
+            hi.B = a.B + (size_t)lo.Nout * a.TR * a.TS * a.Cin;
+            hi.D = a.D + lo.Nout;
+            hipError_t e = launch_igemm_dma(lo, std::is_same<T, BF16>::value, 0, stream);
+            if (e != hipSuccess) return e;
+            return launch_igemm_dma(hi, std::is_same<T, BF16>::value, rem <= 64 ? 3 : 2, stream);
+        }
+        return launch_igemm_dma(b, std::is_same<T, BF16>::value, cfg - 100, stream);
+    }
+    switch (cfg) {
+        case 0: return launch_vec<T, 128, 32, 32, 4, 1, 2>(a, stream);
+        case 1: return launch_vec<T, 128, 64, 32, 2, 2, 2>(a, stream);
+        case 2: return launch_vec<T, 128, 128, 32, 2, 2, 2>(a, stream);
+        case 3: return launch_vec<T, 128, 128, 64, 2, 2, 2>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream)

@@ -1,0 +1,272 @@
+// Implicit-GEMM convolution engine, direct-to-LDS variant (gfx950).
+//
+// Same GEMM view and tap addressing as the register-staged engine, but the
+// activation and filter tiles travel global -> LDS without passing through
+// registers: every wave issues `buffer_load_dwordx4 ... lds` instructions,
+// each of which deposits 64 lanes x 16 bytes = 1 KB (16 tile rows of 32
+// reduction elements) contiguously in LDS.  Out-of-range offsets (zero
+// padding, ragged edges, steps past the end of the reduction) deposit zeros.
+// A ring of four LDS buffers keeps three reduction steps in flight; one
+// barrier per step.  Because the LDS image of a load is contiguous, bank
+// conflicts are avoided by swizzling which 16-byte slice of a row each lane
+// fetches instead of padding the row pitch.
+//
+// Two reduction orders:
+//   tap-major      kk = (tap*Cin + c) runs linearly; a 32-deep step may
+//                  straddle taps.  Any Cin % 8 == 0.
+//   channel-major  for each 32-channel chunk all taps are visited in turn, so
+//                  a workgroup re-reads the same few input rows tap after tap
+//                  while they are cached, and everything that changes from
+//                  step to step is wave-uniform: the per-lane work per load is
+//                  one add and one select.  Whether a tap of a row falls into
+//                  the padding is looked up in a per-row bit mask built once.
+//                  A ragged last chunk is zero-filled.  Needs <= 64 taps.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dlk {
+
+// Row r of a tile is 64 bytes = 4 slices of 16 bytes.  Logical slice v of row
+// r lives at physical slice v ^ ((r >> 2) & 3).  A 16-byte LDS read is served
+// 16 lanes (256 bytes, 64 banks) per cycle; the 16 consecutive rows such a
+// group reads at one logical slice then fall on 16 different 16-byte bank
+// groups: 4*(r & 3) + (v ^ (r >> 2)).  (Measured: twice the read rate of the
+// 2-way conflict of an 8-row rule, four times an unswizzled 64-byte pitch.)
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+
+template <class T, int BM, int BN, int WM, int WN, bool CMAJOR>
+__global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs p)
+{
+    constexpr int NW = WM * WN;
+    constexpr int STAGES = 4;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int AIW = BM / 16 / NW, BIW = BN / 16 / NW;   // load instructions per wave per step
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "every wave must issue the same number of loads");
+    static_assert(TM >= 1 && TN >= 1, "wave tile too small");
+    constexpr int IN_FLIGHT = (STAGES - 2) * (AIW + BIW);   // loads that may still be pending at the wait
+
+    // One array per ring slot.
+    __shared__ __align__(16) uint16_t sA0[BM * BK], sA1[BM * BK], sA2[BM * BK], sA3[BM * BK];
+    __shared__ __align__(16) uint16_t sB0[BN * BK], sB1[BN * BK], sB2[BN * BK], sB3[BN * BK];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int M = p.NB * p.OH * p.OW;
+    const int NT = p.TR * p.TS;                       // taps
+    const int Kred = NT * p.Cin;
+    const int tiles_n = (p.Nout + BN - 1) / BN;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
+    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)p.Nout * Kred * 2u);
+
+    // ---- what this lane fetches: row (16*inst + lane/4), logical slice vec --
+    const int lrow = lane >> 2;                          // row within a 16-row load
+    const int vec = (lane & 3) ^ swz(lrow);              // same for every load of this lane
+    int a_ih[AIW], a_iw[AIW];
+    uint32_t a_off[AIW];                                 // byte offset of (row's tap (0,0) pixel, channel 8*vec)
+    uint32_t a_mask_lo[AIW], a_mask_hi[AIW];             // channel-major: bit t = tap t of this row is inside the image
+#pragma unroll
+    for (int i = 0; i < AIW; ++i) {
+        const int m = m0 + (wave + i * NW) * 16 + lrow;
+        a_mask_lo[i] = a_mask_hi[i] = 0u;
+        if (m < M) {
+            const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+            const int oh = rem / p.OW, ow = rem - oh * p.OW;
+            a_ih[i] = oh * p.sh + p.th0;
+            a_iw[i] = ow * p.sw + p.tw0;
+            a_off[i] = (uint32_t)(((n * p.IH + a_ih[i]) * p.IW + a_iw[i]) * p.Cin + vec * 8) * 2u;
+            if constexpr (CMAJOR) {
+                for (int t = 0; t < NT; ++t) {
+                    const int jr = t / p.TS, js = t - jr * p.TS;
+                    const int ih = a_ih[i] + jr * p.dth, iw = a_iw[i] + js * p.dtw;
+                    const uint32_t in = ((unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW) ? 1u : 0u;
+                    if (t < 32) a_mask_lo[i] |= in << t;
+                    else a_mask_hi[i] |= in << (t - 32);
+                }
+            }
+        } else {
+            a_off[i] = 0;
+            a_ih[i] = -(1 << 28);                        // fails every bounds test
+            a_iw[i] = 0;
+        }
+    }
+    uint32_t b_off[BIW];                                 // byte offset of (filter row, reduction index 8*vec)
+    bool b_ok[BIW];
+#pragma unroll
+    for (int i = 0; i < BIW; ++i) {
+        const int j = n0 + (wave + i * NW) * 16 + lrow;
+        b_ok[i] = j < p.Nout;
+        b_off[i] = ((uint32_t)j * (uint32_t)Kred + vec * 8) * 2u;
+    }
+
+    // ---- reduction cursor ---------------------------------------------------
+    // channel-major: (t, jr, js, c0) are wave-uniform; tap-major: (kk, c, js, jr) per lane
+    int t = 0, jr = 0, js = 0, c0 = 0;
+    int kk = vec * 8, c = 0;
+    if constexpr (!CMAJOR) { c = kk % p.Cin; js = (kk / p.Cin) % p.TS; jr = (kk / p.Cin) / p.TS; }
+    const int lane_c = vec * 8;
+
+    // Issue the loads of the next reduction step into ring slot (sa, sb).
+    auto issue = [&](uint16_t *sa, uint16_t *sb) {
+        if constexpr (CMAJOR) {
+            const uint32_t tap_a = (uint32_t)(((jr * p.dth) * p.IW + js * p.dtw) * p.Cin + c0) * 2u;   // uniform
+            const uint32_t tap_b = (uint32_t)(t * p.Cin + c0) * 2u;                                    // uniform
+            const bool cin = lane_c < p.Cin - c0;        // false only in a ragged last chunk / past the end
+#pragma unroll
+            for (int i = 0; i < AIW; ++i) {
+                const uint32_t word = t < 32 ? a_mask_lo[i] : a_mask_hi[i];
+                const bool ok = cin && ((word >> (t & 31)) & 1u);
+                dma_load_16B(rsA, lds_addr(sa) + (wave + i * NW) * 16 * BK * 2, ok ? a_off[i] + tap_a : OOB_OFFSET);
+            }
+#pragma unroll
+            for (int i = 0; i < BIW; ++i)
+                dma_load_16B(rsB, lds_addr(sb) + (wave + i * NW) * 16 * BK * 2,
+                             (cin && b_ok[i]) ? b_off[i] + tap_b : OOB_OFFSET);
+            ++t;
+            if (++js == p.TS) { js = 0; ++jr; }
+            if (t == NT) { t = 0; jr = 0; js = 0; c0 += BK; }
+        } else {
+            const bool kin = kk < Kred;
+            const int dh = jr * p.dth, dw = js * p.dtw;
+            const uint32_t tap_a = (uint32_t)((dh * p.IW + dw) * p.Cin + (c - lane_c)) * 2u;
+#pragma unroll
+            for (int i = 0; i < AIW; ++i) {
+                const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+                const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+                dma_load_16B(rsA, lds_addr(sa) + (wave + i * NW) * 16 * BK * 2, ok ? a_off[i] + tap_a : OOB_OFFSET);
+            }
+#pragma unroll
+            for (int i = 0; i < BIW; ++i)
+                dma_load_16B(rsB, lds_addr(sb) + (wave + i * NW) * 16 * BK * 2,
+                             (kin && b_ok[i]) ? b_off[i] + (uint32_t)(kk - lane_c) * 2u : OOB_OFFSET);
+            kk += BK;
+            c += BK;
+            while (c >= p.Cin) {
+                c -= p.Cin;
+                if (++js == p.TS) { js = 0; ++jr; }
+            }
+        }
+    };
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // fragment addressing: row (lane % 32) of a 32-row MFMA tile, slices 2*ks + lane/32
+    const int frow = lane & 31;
+    const int fsw = swz(frow);                           // tile bases are multiples of 32 rows
+    int foff[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) foff[ks] = frow * BK + (((ks * 2 + (lane >> 5)) ^ fsw) << 3);
+
+    // MFMAs of one slot (two 16-deep slices); the fragments of both slices are
+    // requested from LDS before the first MFMA is issued.
+    auto load_frags = [&](u32x4_t (&a)[TM], u32x4_t (&b)[TN], const uint16_t *sa, const uint16_t *sb, int ks) {
+        const uint16_t *wa = sa + wm * TM * 32 * BK + foff[ks], *wb = sb + wn * TN * 32 * BK + foff[ks];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const u32x4_t *>(wa + i * 32 * BK);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4_t *>(wb + j * 32 * BK);
+    };
+    auto mma = [&](const uint16_t *sa, const uint16_t *sb) {
+        u32x4_t fa[2][TM], fb[2][TN];
+        load_frags(fa[0], fb[0], sa, sb, 0);
+        load_frags(fa[1], fb[1], sa, sb, 1);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fa[s][i], fb[s][j], acc[i][j]);
+    };
+
+    // Wait until this wave's loads for the oldest pending step have landed,
+    // then meet the other waves: after the barrier the step's tile is complete
+    // in LDS and nobody still reads the slot that is refilled next.
+    auto wait_and_sync = [&]() {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+    };
+
+    // The step count is rounded up to a whole turn of the ring (the extra
+    // steps load and multiply zeros) so that the unrolled loop has one exit.
+    const int nk = CMAJOR ? ((p.Cin + BK - 1) / BK) * NT : (Kred + BK - 1) / BK;
+    const int nturns = (nk + STAGES - 1) / STAGES;
+    if (nk > 0) {
+        issue(sA0, sB0);
+        issue(sA1, sB1);
+        issue(sA2, sB2);
+        for (int turn = 0; turn < nturns; ++turn) {
+            wait_and_sync(); issue(sA3, sB3); mma(sA0, sB0);
+            wait_and_sync(); issue(sA0, sB0); mma(sA1, sB1);
+            wait_and_sync(); issue(sA1, sB1); mma(sA2, sB2);
+            wait_and_sync(); issue(sA2, sB2); mma(sA3, sB3);
+        }
+        // drain the (all-zero) loads issued past the end before the block retires its LDS
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+
+    // ---- epilogue: round once, 32 lanes write 32 consecutive channels -----
+    const bool dense = (p.osh == 1 && p.osw == 1 && p.FH == p.OH && p.FW == p.OW);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + (wm * TM + i) * 32 + acc_row(v, lane);
+            if (m >= M) continue;
+            size_t row_off;
+            if (dense) {
+                row_off = (size_t)m * p.ldd;
+            } else {
+                const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+                const int oh = rem / p.OW, ow = rem - oh * p.OW;
+                row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
+            }
+        }
+    }
+}
+
+template <class T, int BM, int BN, int WM, int WN>
+static hipError_t launch_dma_cfg(const IgemmArgs &a, hipStream_t stream)
+{
+    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    const int64_t tiles = ((M + BM - 1) / BM) * ((a.Nout + BN - 1) / BN);
+    if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)tiles), block(WM * WN * 64);
+    if (a.c_outer)
+        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class T>
+static hipError_t dispatch_dma(const IgemmArgs &a, int cfg, hipStream_t stream)
+{
+    switch (cfg) {
+        case 0: return launch_dma_cfg<T, 256, 256, 2, 4>(a, stream);   // 8 waves, wave tile 128x64
+        case 2: return launch_dma_cfg<T, 128, 128, 2, 2>(a, stream);   // 4 waves, wave tile 64x64
+        case 3: return launch_dma_cfg<T, 128, 64, 2, 2>(a, stream);    // 4 waves, wave tile 64x32
+        case 4: return launch_dma_cfg<T, 64, 32, 2, 1>(a, stream);     // 2 waves, wave tile 32x32
+        case 8: return launch_dma_cfg<T, 64, 64, 2, 1>(a, stream);     // 2 waves, wave tile 32x64
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream_t stream)
+{
+    return is_bf16 ? dispatch_dma<BF16>(a, cfg, stream) : dispatch_dma<F16>(a, cfg, stream);
+}
+
+}  // namespace dlk

@@ -27,10 +27,14 @@ struct IgemmArgs {
     int32_t sh, sw;
     int32_t th0, dth, tw0, dtw;
     int32_t FH, FW, osh, osw, ooh, oow, ldd;
+    int32_t c_outer;            // direct-to-LDS engine only: channel-major reduction order
 };
 
 // is_bf16 selects the MFMA flavour and the output rounding.
 hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+
+// Direct-to-LDS variant of the engine (needs Cin % 8 == 0); cfg selects the tile.
+hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream_t stream);
 
 // Filter re-layout for the data gradient: for one stride-parity class,
 //   wt[c][jr][js][k] = w[k][r0 + jr*rstep][s0 + js*sstep][c]
@@ -55,6 +59,18 @@ struct WgradArgs {
 };
 hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream);
 
+// Direct-to-LDS variant (needs K % 8 == 0 and C % 8 == 0); cfg selects the tile.
+hipError_t launch_wgrad_dma(const WgradArgs &a, bool is_bf16, int cfg, hipStream_t stream);
+
+// Kernel choice and reduction split for one filter gradient, shared by the
+// workspace query and the launch.  cfg < 0: register-staged kernel.
+struct WgradPlan {
+    int cfg;
+    int splits;
+    int chunk;                  // pixels per slice, multiple of 32
+};
+WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC);
+
 // dw[i] = sum_z partial[z][i] in ascending z, rounded to out_dtype (dl_dtype).
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                 hipStream_t stream);
@@ -65,7 +81,5 @@ hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_
                               float scale, int64_t n_pixels, float *loss, uint16_t *dlogits, float *partials,
                               hipStream_t stream);
 
-// Heuristic shared by the workspace query and the launch.
-int wgrad_pick_splits(int64_t npix, int K, int RSC);
 
 }  // namespace dlk

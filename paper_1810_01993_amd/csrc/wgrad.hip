@@ -181,7 +181,7 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_kernel(const WgradArgs p)
         for (int kt = 0; kt < nk; ++kt) {
             const int cb = kt & 1;
             if (kt + 1 < nk) load_tiles();
-            mma_step<T, TM, TN>(sA + cb * BM * LDS_PITCH + wm * TM * 32 * LDS_PITCH,
+            mma_step<T, TM, TN, BK>(sA + cb * BM * LDS_PITCH + wm * TM * 32 * LDS_PITCH,
                                 sB + cb * BN * LDS_PITCH + wn * TN * 32 * LDS_PITCH, lane, acc);
             if (kt + 1 < nk) store_tiles(cb ^ 1);
             __syncthreads();
@@ -201,19 +201,6 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_kernel(const WgradArgs p)
                 if (col < RSC) out[(size_t)k * RSC + col] = acc[i][j][v];
             }
         }
-}
-
-int wgrad_pick_splits(int64_t npix, int K, int RSC)
-{
-    // Enough workgroups to fill 256 CUs about four times over, at least 64
-    // pixels per slice, never more than 256 slices.
-    const int64_t tiles = (int64_t)((K + 127) / 128) * ((RSC + 127) / 128);
-    int64_t s = (1024 + tiles - 1) / tiles;
-    const int64_t max_by_len = (npix + 63) / 64;
-    if (s > max_by_len) s = max_by_len;
-    if (s > 256) s = 256;
-    if (s < 1) s = 1;
-    return (int)s;
 }
 
 template <class T, int BM, int BN, int WM, int WN>
@@ -242,15 +229,39 @@ hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 }
 
 // ---- ordered reduction of the split partials ------------------------------
+// Workgroup = 64 outputs x 4 slice groups.  Thread (x, g) adds slices g, g+4,
+// g+8, ... in ascending order with four independent running sums (so that
+// several loads are in flight), combines them in a fixed order, and the four
+// groups are then added in ascending g through LDS: the summation tree depends
+// only on `splits`, never on timing.
 template <int OUT>   // 0 f16, 1 bf16, 2 f32
-__global__ void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n, void *out)
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n,
+                                                            void *out)
 {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0.f;
-        for (int z = 0; z < splits; ++z) s += partial[(size_t)z * n + i];
-        if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
-        else if constexpr (OUT == 1) reinterpret_cast<uint16_t *>(out)[i] = BF16::from_float(s);
-        else reinterpret_cast<float *>(out)[i] = s;
+    __shared__ float part[4][64];
+    const int x = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int64_t base = (int64_t)blockIdx.x * 64; base < n; base += (int64_t)gridDim.x * 64) {
+        const int64_t i = base + x;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        if (i < n) {
+            int z = g;
+            for (; z + 12 < splits; z += 16) {
+                s0 += partial[(size_t)z * n + i];
+                s1 += partial[(size_t)(z + 4) * n + i];
+                s2 += partial[(size_t)(z + 8) * n + i];
+                s3 += partial[(size_t)(z + 12) * n + i];
+            }
+            for (; z < splits; z += 4) s0 += partial[(size_t)z * n + i];
+        }
+        part[g][x] = (s0 + s1) + (s2 + s3);
+        __syncthreads();
+        if (g == 0 && i < n) {
+            const float s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
+            else if constexpr (OUT == 1) reinterpret_cast<uint16_t *>(out)[i] = BF16::from_float(s);
+            else reinterpret_cast<float *>(out)[i] = s;
+        }
+        __syncthreads();
     }
 }
 
@@ -258,8 +269,8 @@ hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n,
                                 hipStream_t stream)
 {
     if (n <= 0) return hipSuccess;
-    const int64_t want = (n + 255) / 256;
-    const dim3 grid((unsigned)(want < 8192 ? want : 8192)), block(256);
+    const int64_t want = (n + 63) / 64;
+    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
     if (out_dtype == 0) hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out);
     else if (out_dtype == 1) hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out);
     else hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out);
