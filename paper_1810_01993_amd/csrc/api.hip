@@ -67,15 +67,106 @@ AxisTaps class_taps(int a, int R, int stride, int pad, int dil)
     return t;
 }
 
-size_t dgrad_workspace(const dl_conv_desc *d)
+// ---- one implicit GEMM, with the halo-tile kernel where it applies ------------
+// Where the coefficients of the GEMM's filter operand live in the caller's
+// filter tensor: element (row j, tap (jr, js), reduction channel c) is
+// src[base + j*sj + jr*sr + js*ss + c*sc].
+struct FilterSrc { const uint16_t *src; int64_t base, sj, sr, ss, sc; };
+
+// Leading output columns the halo-tile kernel takes (0 = none).  A trailing
+// remainder narrower than its tile goes to the plain engine.
+int halo_columns(const dlk::IgemmArgs &a)
 {
-    // one re-laid-out filter slice per stride-parity class, each 256-byte aligned
+    if (dlk::igemm_use_halo(a)) return a.Nout;
+    if (a.Nout > 256 && a.Nout % 256 != 0) {
+        dlk::IgemmArgs h = a;
+        h.Nout = a.Nout - a.Nout % 256;
+        if (dlk::igemm_use_halo(h)) return h.Nout;
+    }
+    return 0;
+}
+
+size_t igemm_scratch_bytes(const dlk::IgemmArgs &a)
+{
+    const int cols = halo_columns(a);
+    if (!cols) return 0;
+    dlk::IgemmArgs h = a;
+    h.Nout = cols;
+    return align_up(dlk::igemm_blocked_filter_bytes(h), 256);
+}
+
+// a.B: plain [Nout][taps*Cin] filter (may be null if the halo kernel takes every column).
+hipError_t run_igemm(const dlk::IgemmArgs &a, bool bf16, const FilterSrc &fs, uint16_t *scratch, hipStream_t stream)
+{
+    const int cols = halo_columns(a);
+    if (!cols) return dlk::launch_igemm(a, bf16, stream);
+    dlk::FilterBlockArgs f{};
+    f.src = fs.src; f.dst = scratch;
+    f.base = fs.base; f.sj = fs.sj; f.sr = fs.sr; f.ss = fs.ss; f.sc = fs.sc;
+    f.Nrows = cols; f.TR = a.TR; f.TS = a.TS; f.Cin = a.Cin;
+    hipError_t e = dlk::launch_filter_block(f, stream);
+    if (e != hipSuccess) return e;
+    dlk::IgemmArgs h = a;
+    h.Nout = cols;
+    h.B = scratch;
+    e = dlk::launch_igemm_halo(h, bf16, stream);
+    if (e != hipSuccess || cols == a.Nout) return e;
+    dlk::IgemmArgs r = a;
+    r.Nout = a.Nout - cols;
+    r.B = a.B + (size_t)cols * a.TR * a.TS * a.Cin;
+    r.D = a.D + cols;
+    return dlk::launch_igemm(r, bf16, stream);
+}
+
+dlk::IgemmArgs fwd_args(const dl_conv_desc *d, const Geometry &g)
+{
+    dlk::IgemmArgs a{};
+    a.NB = d->N; a.IH = d->H; a.IW = d->W; a.Cin = d->C;
+    a.OH = g.P; a.OW = g.Q; a.Nout = d->K;
+    a.TR = d->R; a.TS = d->S;
+    a.sh = d->stride_h; a.sw = d->stride_w;
+    a.th0 = -d->pad_h; a.dth = d->dil_h; a.tw0 = -d->pad_w; a.dtw = d->dil_w;
+    a.FH = g.P; a.FW = g.Q; a.osh = 1; a.osw = 1; a.ooh = 0; a.oow = 0; a.ldd = d->K;
+    return a;
+}
+
+// The data gradient of one stride-parity class (ca, cb) of the input pixels.
+struct DgradClass {
+    dlk::IgemmArgs args;        // pointers unset
+    AxisTaps th, tw;
+    bool empty, has_taps;
+    size_t wt_bytes, blk_bytes;
+};
+
+DgradClass dgrad_class(const dl_conv_desc *d, const Geometry &g, int ca, int cb)
+{
+    DgradClass c{};
+    const int OH = ca < d->H ? (d->H - ca + d->stride_h - 1) / d->stride_h : 0;
+    const int OW = cb < d->W ? (d->W - cb + d->stride_w - 1) / d->stride_w : 0;
+    c.th = class_taps(ca, d->R, d->stride_h, d->pad_h, d->dil_h);
+    c.tw = class_taps(cb, d->S, d->stride_w, d->pad_w, d->dil_w);
+    c.empty = OH == 0 || OW == 0;
+    c.has_taps = c.th.count > 0 && c.tw.count > 0;
+    c.wt_bytes = align_up((size_t)d->C * c.th.count * c.tw.count * d->K * sizeof(uint16_t), 256);
+    dlk::IgemmArgs &a = c.args;
+    a.NB = d->N; a.IH = g.P; a.IW = g.Q; a.Cin = d->K;
+    a.OH = OH; a.OW = OW; a.Nout = d->C;
+    a.TR = c.has_taps ? c.th.count : 0; a.TS = c.has_taps ? c.tw.count : 1;
+    a.sh = 1; a.sw = 1;
+    a.th0 = c.th.t0; a.dth = c.th.dt; a.tw0 = c.tw.t0; a.dtw = c.tw.dt;
+    a.FH = d->H; a.FW = d->W; a.osh = d->stride_h; a.osw = d->stride_w; a.ooh = ca; a.oow = cb;
+    a.ldd = d->C;
+    c.blk_bytes = (c.empty || !c.has_taps) ? 0 : igemm_scratch_bytes(a);
+    return c;
+}
+
+size_t dgrad_workspace(const dl_conv_desc *d, const Geometry &g)
+{
     size_t total = 0;
-    for (int a = 0; a < d->stride_h; ++a)
-        for (int b = 0; b < d->stride_w; ++b) {
-            const AxisTaps th = class_taps(a, d->R, d->stride_h, d->pad_h, d->dil_h);
-            const AxisTaps tw = class_taps(b, d->S, d->stride_w, d->pad_w, d->dil_w);
-            total += align_up((size_t)d->C * th.count * tw.count * d->K * sizeof(uint16_t), 256);
+    for (int ca = 0; ca < d->stride_h; ++ca)
+        for (int cb = 0; cb < d->stride_w; ++cb) {
+            const DgradClass c = dgrad_class(d, g, ca, cb);
+            total += c.wt_bytes + c.blk_bytes;
         }
     return total;
 }
@@ -129,8 +220,8 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
     const dl_status st = check_desc(desc, &g);
     if (st != DL_OK) return st;
     switch (pass) {
-        case DL_PASS_FWD: *bytes = 0; return DL_OK;
-        case DL_PASS_BWD_DATA: *bytes = dgrad_workspace(desc); return DL_OK;
+        case DL_PASS_FWD: *bytes = igemm_scratch_bytes(fwd_args(desc, g)); return DL_OK;
+        case DL_PASS_BWD_DATA: *bytes = dgrad_workspace(desc, g); return DL_OK;
         case DL_PASS_BWD_FILTER: *bytes = wgrad_workspace(desc, g); return DL_OK;
     }
     return DL_ERR_UNSUPPORTED;
@@ -139,25 +230,21 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
 dl_status conv2d_fwd(const dl_conv_desc *d, const void *x, const void *w, void *y, void *workspace,
                      size_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!d || !x || !w || !y) return DL_ERR_NULL;
     Geometry g;
     const dl_status st = check_desc(d, &g);
     if (st != DL_OK) return st;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return DL_ERR_ALIGN;
-
-    dlk::IgemmArgs a{};
+    dlk::IgemmArgs a = fwd_args(d, g);
+    const size_t need = igemm_scratch_bytes(a);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return DL_ERR_WORKSPACE;
+    if (need > 0 && !aligned16(workspace)) return DL_ERR_ALIGN;
     a.A = static_cast<const uint16_t *>(x);
     a.B = static_cast<const uint16_t *>(w);
     a.D = static_cast<uint16_t *>(y);
-    a.NB = d->N; a.IH = d->H; a.IW = d->W; a.Cin = d->C;
-    a.OH = g.P; a.OW = g.Q; a.Nout = d->K;
-    a.TR = d->R; a.TS = d->S;
-    a.sh = d->stride_h; a.sw = d->stride_w;
-    a.th0 = -d->pad_h; a.dth = d->dil_h; a.tw0 = -d->pad_w; a.dtw = d->dil_w;
-    a.FH = g.P; a.FW = g.Q; a.osh = 1; a.osw = 1; a.ooh = 0; a.oow = 0; a.ldd = d->K;
-    return hip_status(dlk::launch_igemm(a, d->dtype == DL_BF16, static_cast<hipStream_t>(hip_stream)));
+    const FilterSrc fs{a.B, 0, (int64_t)d->R * d->S * d->C, (int64_t)d->S * d->C, d->C, 1};
+    return hip_status(run_igemm(a, d->dtype == DL_BF16, fs, static_cast<uint16_t *>(workspace),
+                                static_cast<hipStream_t>(hip_stream)));
 }
 
 dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, void *dx, void *workspace,
@@ -168,49 +255,43 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
     const dl_status st = check_desc(d, &g);
     if (st != DL_OK) return st;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return DL_ERR_ALIGN;
-    const size_t need = dgrad_workspace(d);
+    const size_t need = dgrad_workspace(d, g);
     if (need > 0 && (!workspace || workspace_bytes < need)) return DL_ERR_WORKSPACE;
     if (need > 0 && !aligned16(workspace)) return DL_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool bf16 = d->dtype == DL_BF16;
 
     // Input pixels (h, w) fall into stride_h*stride_w parity classes; within a
     // class the contributing taps and the output pixels they pair with form
-    // regular grids, so each class is one dense implicit GEMM over dy.
+    // regular grids, so each class is one dense implicit GEMM over dy with the
+    // filter re-laid-out as [c][tap][k].
     size_t ws_off = 0;
     for (int ca = 0; ca < d->stride_h; ++ca)
         for (int cb = 0; cb < d->stride_w; ++cb) {
-            const int OH = ca < d->H ? (d->H - ca + d->stride_h - 1) / d->stride_h : 0;
-            const int OW = cb < d->W ? (d->W - cb + d->stride_w - 1) / d->stride_w : 0;
-            const AxisTaps th = class_taps(ca, d->R, d->stride_h, d->pad_h, d->dil_h);
-            const AxisTaps tw = class_taps(cb, d->S, d->stride_w, d->pad_w, d->dil_w);
-            const size_t slice = align_up((size_t)d->C * th.count * tw.count * d->K * sizeof(uint16_t), 256);
+            DgradClass c = dgrad_class(d, g, ca, cb);
             uint16_t *wt = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + ws_off);
-            ws_off += slice;
-            if (OH == 0 || OW == 0) continue;
-            const bool has_taps = th.count > 0 && tw.count > 0;
-            if (has_taps) {
+            uint16_t *blk = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + ws_off + c.wt_bytes);
+            ws_off += c.wt_bytes + c.blk_bytes;
+            if (c.empty) continue;
+            dlk::IgemmArgs &a = c.args;
+            a.A = static_cast<const uint16_t *>(dy);
+            a.D = static_cast<uint16_t *>(dx);
+            a.B = static_cast<const uint16_t *>(w);     // never read when there are no taps
+            const bool all_halo = c.has_taps && halo_columns(a) == a.Nout;
+            if (c.has_taps && !all_halo) {
                 dlk::FilterRelayoutArgs f{};
                 f.w = static_cast<const uint16_t *>(w);
                 f.wt = wt;
                 f.K = d->K; f.R = d->R; f.S = d->S; f.C = d->C;
-                f.r0 = th.r0; f.rstep = th.rstep; f.TR = th.count;
-                f.s0 = tw.r0; f.sstep = tw.rstep; f.TS = tw.count;
-                const hipError_t e = dlk::launch_filter_relayout(f, stream);
-                if (e != hipSuccess) return DL_ERR_LAUNCH;
+                f.r0 = c.th.r0; f.rstep = c.th.rstep; f.TR = c.th.count;
+                f.s0 = c.tw.r0; f.sstep = c.tw.rstep; f.TS = c.tw.count;
+                if (dlk::launch_filter_relayout(f, stream) != hipSuccess) return DL_ERR_LAUNCH;
+                a.B = wt;
             }
-            dlk::IgemmArgs a{};
-            a.A = static_cast<const uint16_t *>(dy);
-            a.B = has_taps ? wt : static_cast<const uint16_t *>(w);   // never read when there are no taps
-            a.D = static_cast<uint16_t *>(dx);
-            a.NB = d->N; a.IH = g.P; a.IW = g.Q; a.Cin = d->K;
-            a.OH = OH; a.OW = OW; a.Nout = d->C;
-            a.TR = has_taps ? th.count : 0; a.TS = has_taps ? tw.count : 1;
-            a.sh = 1; a.sw = 1;
-            a.th0 = th.t0; a.dth = th.dt; a.tw0 = tw.t0; a.dtw = tw.dt;
-            a.FH = d->H; a.FW = d->W; a.osh = d->stride_h; a.osw = d->stride_w; a.ooh = ca; a.oow = cb;
-            a.ldd = d->C;
-            const hipError_t e = dlk::launch_igemm(a, d->dtype == DL_BF16, stream);
-            if (e != hipSuccess) return DL_ERR_LAUNCH;
+            const int64_t SC = (int64_t)d->S * d->C;
+            const FilterSrc fs{static_cast<const uint16_t *>(w), c.th.r0 * SC + (int64_t)c.tw.r0 * d->C, 1,
+                               c.th.rstep * SC, (int64_t)c.tw.rstep * d->C, (int64_t)d->R * SC};
+            if (run_igemm(a, bf16, fs, blk, stream) != hipSuccess) return DL_ERR_LAUNCH;
         }
     return DL_OK;
 }

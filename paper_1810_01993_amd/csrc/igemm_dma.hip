@@ -191,7 +191,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     // then meet the other waves: after the barrier the step's tile is complete
     // in LDS and nobody still reads the slot that is refilled next.
     auto wait_and_sync = [&]() {
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
     };
 
     // The step count is rounded up to a whole turn of the ring (the extra

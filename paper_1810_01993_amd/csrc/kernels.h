@@ -36,6 +36,22 @@ hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 // Direct-to-LDS variant of the engine (needs Cin % 8 == 0); cfg selects the tile.
 hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream_t stream);
 
+// Halo-tile variant for stride-1 multi-tap filters.  a.B must point at the
+// blocked filter copy [chunk][tap][a.Nout][32] made by launch_filter_block.
+bool igemm_use_halo(const IgemmArgs &a);
+size_t igemm_blocked_filter_bytes(const IgemmArgs &a);
+hipError_t launch_igemm_halo(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+
+// dst[((chunk*TR*TS + jr*TS + js)*Nrows + j)*32 + e] = src[base + j*sj + jr*sr + js*ss + (chunk*32+e)*sc],
+// zero where chunk*32 + e >= Cin.
+struct FilterBlockArgs {
+    const uint16_t *src;
+    uint16_t *dst;
+    int64_t base, sj, sr, ss, sc;
+    int32_t Nrows, TR, TS, Cin;
+};
+hipError_t launch_filter_block(const FilterBlockArgs &a, hipStream_t stream);
+
 // Filter re-layout for the data gradient: for one stride-parity class,
 //   wt[c][jr][js][k] = w[k][r0 + jr*rstep][s0 + js*sstep][c]
 struct FilterRelayoutArgs {

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_dma_kernel(const WgradArgs 
         }
     };
     auto wait_and_sync = [&]() {
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
     };
 
     // The step count is rounded up to a whole turn of the ring (the extra

@@ -112,6 +112,22 @@ def test_big_tile_path(api):
     check_layer(api, L("bigtile", 2, 192, 288, 16, 256, 3, 3, 1, 1, 1), "f16", synth.seed_for(0, 501))
 
 
+# Shapes that take the halo-tile kernel (stride 1, several taps, >= 160 output
+# columns, >= 200 patches): ragged patches, ragged channel chunk, dilation 2,
+# a column remainder handed to the plain engine, both data types.
+HALO = [
+    (L("halo.ragged", 2, 150, 170, 40, 256, 3, 3, 1, 1, 1), "f16"),
+    (L("halo.d2.n192", 1, 230, 250, 32, 192, 3, 3, 1, 2, 2), "bf16"),
+    (L("halo.dgrad.c304", 1, 230, 250, 304, 32, 3, 3, 1, 1, 1), "f16"),
+    (L("halo.5x5.nopad", 1, 240, 260, 16, 160, 5, 5, 1, 0, 1), "bf16"),
+]
+
+
+@pytest.mark.parametrize("layer,dtype", HALO, ids=[l.name for l, _ in HALO])
+def test_halo_tile_kernel(api, layer, dtype):
+    check_layer(api, layer, dtype, synth.seed_for(0, 600 + len(layer.name)), x_kind="normal", n_samples=8192)
+
+
 def test_fp32_filter_gradient(api):
     layer = L("dw32", 2, 19, 23, 24, 40, 3, 3, 1, 1, 1)
     (x32, xb), _, (dy32, dyb) = U.conv_inputs(layer, "bf16", 77, "normal")
