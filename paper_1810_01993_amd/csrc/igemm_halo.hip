@@ -135,11 +135,16 @@ __global__ __launch_bounds__(512) void igemm_halo_kernel(const IgemmArgs p)
     }
     const int v0 = lane >> 5;                            // slice of ks = 0; ks = 1 is v0 + 2
 
-    auto mma = [&](const uint16_t *sb) {
+    // The eight waves work in two groups of four (one wave of each group per
+    // SIMD) that run half a step apart: while one group reads its fragments
+    // from LDS and issues the next loads, the other keeps the matrix pipe busy,
+    // and at the next barrier they swap.  Each step therefore has two barriers;
+    // group 1 takes one extra barrier before the loop and group 0 one after it.
+    u32x4_t fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const uint16_t *sb) {
         const int shift = (p.th0 + jr * p.dth - oy_min) * HW + (p.tw0 + js * p.dtw - ox_min);   // uniform
         const uint16_t *hal = &sH[chunk & 1][0];
         const uint16_t *wb = sb + wn * TN * 32 * BK;
-        u32x4_t fa[2][TM], fb[2][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int h = hb[i] + shift;
@@ -151,28 +156,44 @@ __global__ __launch_bounds__(512) void igemm_halo_kernel(const IgemmArgs p)
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int j = 0; j < TN; ++j) fb[ks][j] = *reinterpret_cast<const u32x4_t *>(wb + j * 32 * BK + foff[ks]);
+    };
+    auto multiply = [&]() {
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fa[s][i], fb[s][j], acc[i][j]);
-        // advance the multiply cursor
+    };
+    auto advance = [&]() {
         ++t;
         if (++js == p.TS) { js = 0; ++jr; }
         if (t == NT) { t = 0; jr = 0; js = 0; ++chunk; }
     };
-    auto wait_and_sync = [&]() {
+    // Barrier that opens a read phase: this wave's loads for the step about to be read have
+    // landed (two later steps may be in flight) and its own LDS reads are complete.
+    auto sync_loaded = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        __builtin_amdgcn_sched_barrier(0);
     };
-    // One step: after the barrier, refill the ring slot freed by the previous step with the
-    // filter tile three steps ahead, fetch one piece of the next chunk's halo, multiply.
+    auto sync_phase = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // One step of one wave: read this step's fragments, refill the ring slot freed by the
+    // previous step with the filter tile three steps ahead, fetch one piece of the next
+    // chunk's halo; then, one phase later, multiply.
     auto step = [&](uint16_t *sb_refill, const uint16_t *sb_cur) {
-        wait_and_sync();
+        sync_loaded();
+        read_frags(sb_cur);
         issue_filter(sb_refill);
         if (t < AW) issue_halo_piece(t, chunk + 1);
         else issue_spare();
-        mma(sb_cur);
+        advance();
+        sync_phase();
+        multiply();
     };
 
     const int nk = nchunks * NT;
@@ -183,12 +204,15 @@ __global__ __launch_bounds__(512) void igemm_halo_kernel(const IgemmArgs p)
     issue_filter(sB0); issue_spare();
     issue_filter(sB1); issue_spare();
     issue_filter(sB2); issue_spare();
+    const bool late_group = wave >= NW / 2;              // waves 4..7: the second wave on each SIMD
+    if (late_group) sync_loaded();
     for (int turn = 0; turn < nturns; ++turn) {
         step(sB3, sB0);
         step(sB0, sB1);
         step(sB1, sB2);
         step(sB2, sB3);
     }
+    if (!late_group) sync_phase();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue ---------------------------------------------------------------
