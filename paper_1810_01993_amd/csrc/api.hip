@@ -173,7 +173,8 @@ size_t dgrad_workspace(const dl_conv_desc *d, const Geometry &g)
 
 dlk::WgradPlan wgrad_plan(const dl_conv_desc *d, const Geometry &g)
 {
-    return dlk::wgrad_make_plan((int64_t)d->N * g.P * g.Q, d->K, d->C, d->R * d->S * d->C);
+    const bool thin = dlk::thin_wgrad_applicable(d->K, d->C, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w);
+    return dlk::wgrad_make_plan((int64_t)d->N * g.P * g.Q, d->K, d->C, d->R * d->S * d->C, thin);
 }
 
 size_t wgrad_workspace(const dl_conv_desc *d, const Geometry &g)
@@ -317,8 +318,9 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w; a.dh = d->dil_h; a.dw = d->dil_w;
     a.splits = plan.splits;
     a.chunk = plan.chunk;
-    hipError_t e = plan.cfg >= 0 ? dlk::launch_wgrad_dma(a, d->dtype == DL_BF16, plan.cfg, stream)
-                                 : dlk::launch_wgrad(a, d->dtype == DL_BF16, stream);
+    hipError_t e = plan.cfg >= 0    ? dlk::launch_wgrad_dma(a, d->dtype == DL_BF16, plan.cfg, stream)
+                   : plan.cfg == -2 ? dlk::launch_thin_wgrad(a, d->dtype == DL_BF16, stream)
+                                    : dlk::launch_wgrad(a, d->dtype == DL_BF16, stream);
     if (e != hipSuccess) return DL_ERR_LAUNCH;
     e = dlk::launch_splitk_reduce(a.partial, plan.splits, g.w_elems, dw, d->dw_dtype, stream);
     return hip_status(e);

@@ -304,6 +304,7 @@ template <class T>
 static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 {
     const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    if (forced_cfg() < 0 && thin_rows_applicable(a)) return launch_thin_rows(a, std::is_same<T, BF16>::value, stream);
     if (a.Cin % 8 != 0) {
         const int64_t tiles = ((M + 127) / 128) * ((a.Nout + 63) / 64);
         if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;

@@ -85,7 +85,13 @@ struct WgradPlan {
     int splits;
     int chunk;                  // pixels per slice, multiple of 32
 };
-WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC);
+WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok);
+
+// Streaming kernels for 1x1 layers with <= 4 channels on one side (cfg -2 of the plan).
+bool thin_rows_applicable(const IgemmArgs &a);
+hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+bool thin_wgrad_applicable(int K, int C, int R, int S, int sh, int sw, int ph, int pw);
+hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream);
 
 // dw[i] = sum_z partial[z][i] in ascending z, rounded to out_dtype (dl_dtype).
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,

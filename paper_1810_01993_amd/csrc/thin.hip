@@ -1,0 +1,146 @@
+// Streaming kernels for 1x1 convolutions with a handful of channels on one
+// side (the 3-class logits layer): there the data gradient and the filter
+// gradient are bandwidth-bound outer-product / dot-product sweeps over the
+// 256-channel activation tensor, and an MFMA tile padded from 3 to 32 would
+// only add latency.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dlk {
+
+constexpr int THIN_MAX = 4;      // channels on the thin side
+
+// D[m][j..j+7] = sum_{c < Cin} A[m][c] * B[j..j+7][c]   (one tap, dense rows, Cin <= THIN_MAX, Nout % 8 == 0)
+// A thread owns one group of 8 output columns, keeps their filter values in
+// registers and walks down the rows: one 16-byte store per Cin broadcast loads.
+template <class T>
+__global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
+{
+    const int groups = p.Nout / 8;
+    const int gpb = groups < 256 ? groups : 256;         // column groups per workgroup
+    const int rows_pb = 256 / gpb;                       // rows per workgroup pass
+    const int g = blockIdx.y * gpb + threadIdx.x % gpb, r = threadIdx.x / gpb;
+    if (r >= rows_pb || g >= groups) return;
+    const int j = g * 8;
+    float b[8][THIN_MAX];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int c = 0; c < THIN_MAX; ++c) b[e][c] = c < p.Cin ? T::to_float(p.B[(size_t)(j + e) * p.Cin + c]) : 0.f;
+    const int64_t M = (int64_t)p.NB * p.OH * p.OW;
+    const int64_t step = (int64_t)gridDim.x * rows_pb;
+#pragma unroll 4
+    for (int64_t m = (int64_t)blockIdx.x * rows_pb + r; m < M; m += step) {
+        float a[THIN_MAX];
+#pragma unroll
+        for (int c = 0; c < THIN_MAX; ++c) a[c] = c < p.Cin ? T::to_float(p.A[m * p.Cin + c]) : 0.f;
+        u32x4_t out;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int c = 0; c < THIN_MAX; ++c) {
+                s0 += a[c] * b[e][c];
+                s1 += a[c] * b[e + 1][c];
+            }
+            out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+        }
+        *reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j) = out;
+    }
+}
+
+bool thin_rows_applicable(const IgemmArgs &a)
+{
+    const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW &&
+                       a.IH == a.OH && a.IW == a.OW;
+    return dense && a.TR == 1 && a.TS == 1 && a.th0 == 0 && a.tw0 == 0 && a.Cin <= THIN_MAX && a.Nout % 8 == 0 &&
+           a.ldd % 8 == 0;
+}
+
+hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
+{
+    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    const int groups = a.Nout / 8;
+    if (M <= 0 || groups <= 0) return hipSuccess;
+    const int gpb = groups < 256 ? groups : 256, rows_pb = 256 / gpb;
+    const int64_t want = (M + rows_pb * 48 - 1) / (rows_pb * 48);   // about 48 rows per thread
+    const dim3 grid((unsigned)(want < 32768 ? want : 32768), (unsigned)((groups + gpb - 1) / gpb)), block(256);
+    if (is_bf16) hipLaunchKernelGGL(thin_rows_kernel<BF16>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(thin_rows_kernel<F16>, grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+// Filter gradient of a 1x1, stride-1, unpadded convolution with K <= THIN_MAX:
+//   partial[b][k][c] = sum over workgroup b's pixels of dy[pix][k] * x[pix][c].
+// A workgroup is (C/8 channel groups) x (256 / (C/8) pixel lanes); every thread
+// keeps K x 8 running sums, the pixel lanes are then added in a fixed order.
+template <class T>
+__global__ __launch_bounds__(256) void thin_wgrad_kernel(const WgradArgs p)
+{
+    __shared__ float red[256 * 8];                       // 8 sums per thread, reused for each k
+    const int groups = p.C / 8;                          // <= 256
+    const int lanes = 256 / groups;                      // pixel lanes per workgroup
+    const int g = threadIdx.x % groups, pl = threadIdx.x / groups;
+    const int npix = p.N * p.P * p.Q;
+    const int pix_begin = blockIdx.x * p.chunk, pix_end = min(npix, pix_begin + p.chunk);
+    float acc[THIN_MAX][8];
+#pragma unroll
+    for (int k = 0; k < THIN_MAX; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[k][e] = 0.f;
+    if (pl < lanes) {
+#pragma unroll 4
+        for (int pix = pix_begin + pl; pix < pix_end; pix += lanes) {
+            const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8);
+            float xf[8];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                xf[2 * d] = T::to_float((uint16_t)(xv[d] & 0xffffu));
+                xf[2 * d + 1] = T::to_float((uint16_t)(xv[d] >> 16));
+            }
+#pragma unroll
+            for (int k = 0; k < THIN_MAX; ++k)
+                if (k < p.K) {
+                    const float gk = T::to_float(p.dy[(size_t)pix * p.K + k]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[k][e] += gk * xf[e];
+                }
+        }
+    }
+    float *out = p.partial + (size_t)blockIdx.x * p.K * p.C;
+    for (int k = 0; k < p.K; ++k) {
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < THIN_MAX; ++kk) if (kk == k) v = acc[kk][e];
+            red[threadIdx.x * 8 + e] = (pl < lanes) ? v : 0.f;
+        }
+        __syncthreads();
+        if (pl == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float s = 0.f;
+                for (int l = 0; l < lanes; ++l) s += red[(l * groups + g) * 8 + e];
+                out[(size_t)k * p.C + g * 8 + e] = s;
+            }
+        }
+    }
+}
+
+bool thin_wgrad_applicable(int K, int C, int R, int S, int sh, int sw, int ph, int pw)
+{
+    return K <= THIN_MAX && R == 1 && S == 1 && sh == 1 && sw == 1 && ph == 0 && pw == 0 && C % 8 == 0 && C / 8 <= 256 &&
+           C >= 8;
+}
+
+hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
+{
+    const dim3 grid((unsigned)a.splits), block(256);
+    if (is_bf16) hipLaunchKernelGGL(thin_wgrad_kernel<BF16>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(thin_wgrad_kernel<F16>, grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace dlk

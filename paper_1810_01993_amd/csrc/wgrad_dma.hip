@@ -226,13 +226,23 @@ static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC)
+WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
 {
     static const int forced = [] {
         const char *e = std::getenv("DLCONV_WGRAD_CFG");      // tuning override, unset in normal use
         return e ? std::atoi(e) : -2;
     }();
     WgradPlan pl{-1, 1, 32};
+    if (thin_ok && forced != -1) {
+        // streaming kernel: one workgroup per slice of pixels, about eight slices per CU
+        int64_t s = (npix + 255) / 256;
+        if (s > 2048) s = 2048;
+        if (s < 1) s = 1;
+        pl.cfg = -2;
+        pl.chunk = (int)((npix + s - 1) / s);
+        pl.splits = (int)((npix + pl.chunk - 1) / pl.chunk);
+        return pl;
+    }
     int bm = 128, bn = 128;
     int64_t target = 1024;                                   // workgroups wanted in flight overall
     const bool dma_ok = K % 8 == 0 && C % 8 == 0 && K >= 32 && RSC >= 64;

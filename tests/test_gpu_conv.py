@@ -87,6 +87,8 @@ SMALL = [
     L("1x1.s2", 2, 18, 20, 64, 160, 1, 1, 2, 0, 1),
     L("1x1.k3", 1, 33, 47, 256, 3, 1, 1, 1, 0, 1),
     L("1x1.k48", 1, 20, 30, 256, 48, 1, 1, 1, 0, 1),
+    L("1x1.k4.c304", 2, 21, 30, 304, 4, 1, 1, 1, 0, 1),
+    L("1x1.k2.c8", 1, 9, 10, 8, 2, 1, 1, 1, 0, 1),
     L("3x3.c304", 1, 12, 40, 304, 256, 3, 3, 1, 1, 1),
     L("3x3.d6.small-map", 2, 10, 14, 64, 32, 3, 3, 1, 6, 6),
     L("3x3.d12.small-map", 1, 12, 18, 32, 64, 3, 3, 1, 12, 12),
