@@ -73,18 +73,7 @@ AxisTaps class_taps(int a, int R, int stride, int pad, int dil)
 // src[base + j*sj + jr*sr + js*ss + c*sc].
 struct FilterSrc { const uint16_t *src; int64_t base, sj, sr, ss, sc; };
 
-// Leading output columns the halo-tile kernel takes (0 = none).  A trailing
-// remainder narrower than its tile goes to the plain engine.
-int halo_columns(const dlk::IgemmArgs &a)
-{
-    if (dlk::igemm_use_halo(a)) return a.Nout;
-    if (a.Nout > 256 && a.Nout % 256 != 0) {
-        dlk::IgemmArgs h = a;
-        h.Nout = a.Nout - a.Nout % 256;
-        if (dlk::igemm_use_halo(h)) return h.Nout;
-    }
-    return 0;
-}
+int halo_columns(const dlk::IgemmArgs &a) { return dlk::igemm_halo_columns(a); }
 
 size_t igemm_scratch_bytes(const dlk::IgemmArgs &a)
 {

@@ -243,23 +243,42 @@ static int halo_pieces_per_wave(const IgemmArgs &a)
     return 0;
 }
 
-bool igemm_use_halo(const IgemmArgs &a)
+static int halo_mode()
 {
     static const int mode = [] {
-        const char *e = std::getenv("DLCONV_HALO");       // tuning override: 0 = never
+        const char *e = std::getenv("DLCONV_HALO");       // tuning override: 0 = never, 2 = general kernel only
         return e ? std::atoi(e) : 1;
     }();
-    if (!mode) return false;
+    return mode;
+}
+
+static bool use_3x3(const IgemmArgs &a) { return halo_mode() == 1 && igemm_halo3x3_applicable(a); }
+
+// Can a halo-tile kernel take all a.Nout columns?
+static bool halo_takes(const IgemmArgs &a)
+{
+    if (!halo_mode() || a.Nout <= 0) return false;
+    if (use_3x3(a)) return igemm_halo3x3_tiles(a) >= 200;
     const int NT = a.TR * a.TS;
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     const int aw = halo_pieces_per_wave(a);
     if (!dense || a.Cin % 8 != 0 || aw == 0 || aw > NT - 2) return false;
-    if (a.Nout < 160) return false;                       // the 256-wide tile would run mostly empty
-    const int rem = a.Nout % HALO_BN;
-    if (rem != 0 && rem < 160 && a.Nout > HALO_BN) return false;
     const int64_t tiles = (int64_t)a.NB * ((a.OH + HALO_TH - 1) / HALO_TH) * ((a.OW + HALO_TW - 1) / HALO_TW) *
                           ((a.Nout + HALO_BN - 1) / HALO_BN);
     return tiles >= 200;
+}
+
+// Leading output columns a halo-tile kernel takes (0 = none).  A trailing
+// remainder that would fill less than about two thirds of a column tile is
+// left to the plain engine.
+int igemm_halo_columns(const IgemmArgs &a)
+{
+    if (!halo_mode()) return 0;
+    const int bn = use_3x3(a) ? 128 : HALO_BN, enough = use_3x3(a) ? 96 : 160;
+    const int rem = a.Nout % bn;
+    IgemmArgs h = a;
+    if (rem != 0 && rem < enough) h.Nout = a.Nout - rem;
+    return halo_takes(h) ? h.Nout : 0;
 }
 
 size_t igemm_blocked_filter_bytes(const IgemmArgs &a)
@@ -272,6 +291,7 @@ hipError_t launch_igemm_halo(const IgemmArgs &a, bool is_bf16, hipStream_t strea
     const int64_t tiles = (int64_t)a.NB * ((a.OH + HALO_TH - 1) / HALO_TH) * ((a.OW + HALO_TW - 1) / HALO_TW) *
                           ((a.Nout + HALO_BN - 1) / HALO_BN);
     if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
+    if (use_3x3(a)) return launch_igemm_halo3x3(a, is_bf16, stream);
     const dim3 grid((unsigned)tiles), block(512);
     const int aw = halo_pieces_per_wave(a);
     if (aw == 3) {

@@ -1,0 +1,246 @@
+// Halo-tile implicit-GEMM kernel specialised for dense 3x3 filters with unit
+// stride and dilation (gfx950): the forward pass and the data gradient of the
+// full-resolution decoder convolutions, where nearly all of the FLOPs are.
+//
+// A workgroup owns a 16-row x 32-column patch of output pixels (GEMM M = 512)
+// and 128 output channels.  Compared with a square 256 x 256 tile the filter
+// operand, which every workgroup has to re-fetch from L2 for every step, is
+// half as wide, while the activation operand costs little because the patch is
+// deposited in LDS once per 32-channel chunk together with its halo
+// (18 x 34 pixels) and then serves all nine taps: 12.4 KB instead of 18.3 KB
+// travel L2 -> LDS per step.
+//
+// The patch is 32 pixels wide so that one 32-row MFMA operand is exactly one
+// patch row.  Moving a tap down by one row then means using the operand
+// registers of the next row: a wave (4 patch rows x 64 channels) reads the six
+// halo rows it needs once per column shift and uses each of them for up to
+// three taps, which cuts the LDS -> register traffic of the activation operand
+// in half.  Taps are therefore visited column shift by column shift, the row
+// shift running fastest.
+//
+// Filter tiles come from the re-laid-out copy [chunk][tap][output channel][32]
+// through a ring of six 8 KB LDS slots (five steps in flight); the halo of the
+// next chunk is fetched in 1 KB pieces during the first five steps of the
+// current one.  Every step issues two loads per wave (a filter piece and a
+// halo piece or its out-of-range stand-in), so one constant wait count serves.
+// The eight waves run as two groups half a step apart, as in the general
+// halo-tile kernel.
+#include <cstdlib>
+#include <type_traits>
+
+#include "device_common.h"
+#include "kernels.h"
+
+namespace dlk {
+
+namespace {
+constexpr int P3_PH = 16, P3_PW = 32, P3_BN = 128;
+constexpr int P3_HH = P3_PH + 2, P3_HW = P3_PW + 2;
+__device__ __forceinline__ int p3_swz(int row) { return (row >> 2) & 3; }
+}  // namespace
+
+template <class T>
+__global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
+{
+    constexpr int NW = 8, WN = 2, TM = 4, TN = 2;        // 4 x 2 waves, wave tile 4 patch rows x 64 channels
+    constexpr int HW = P3_HW, HH = P3_HH, BN = P3_BN;
+    constexpr int NT = 9;
+    constexpr int AW = 5;                                // halo pieces per wave: 5*8*16 = 640 >= 18*34 pixels
+    constexpr int HALO_ROWS = AW * NW * 16;
+    constexpr int S = 6;                                 // filter ring slots
+    constexpr int PER_STEP = 2;
+    constexpr int IN_FLIGHT = (S - 2) * PER_STEP;
+    static_assert(AW <= NT - (S - 2), "a halo piece must have landed before its chunk starts");
+    static_assert(HALO_ROWS >= HH * HW, "halo does not fit its pieces");
+
+    __shared__ __align__(16) uint16_t sH[2][HALO_ROWS * BK];          // halo images, alternating per chunk
+    __shared__ __align__(16) uint16_t sB[S][BN * BK];
+    __shared__ __align__(16) uint16_t sSpare[NW * 16 * BK];           // target of stand-in loads
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int nchunks = (p.Cin + BK - 1) / BK;
+    const bool flip_r = p.dth < 0, flip_s = p.dtw < 0;   // which tap a given shift belongs to
+    const int oy_min = flip_r ? p.th0 - 2 : p.th0, ox_min = flip_s ? p.tw0 - 2 : p.tw0;
+
+    const int tiles_x = (p.OW + P3_PW - 1) / P3_PW, tiles_y = (p.OH + P3_PH - 1) / P3_PH;
+    const int tiles_n = (p.Nout + BN - 1) / BN;
+    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int tn = tile % tiles_n; tile /= tiles_n;
+    const int tx = tile % tiles_x; tile /= tiles_x;
+    const int ty = tile % tiles_y;
+    const int img = tile / tiles_y;
+    const int y0 = ty * P3_PH, x0 = tx * P3_PW, n0 = tn * BN;
+
+    const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
+    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)nchunks * NT * p.Nout * BK * 2u);
+
+    // ---- what this lane fetches ---------------------------------------------
+    const int lrow = lane >> 2;
+    const int vec = (lane & 3) ^ p3_swz(lrow);
+    const int lane_c = vec * 8;
+    uint32_t h_off[AW];                                  // byte offset of (halo pixel, channel 8*vec), or out of range
+#pragma unroll
+    for (int a = 0; a < AW; ++a) {
+        const int hp = (wave + a * NW) * 16 + lrow;
+        const int hy = hp / HW, hx = hp - hy * HW;
+        const int iy = y0 + oy_min + hy, ix = x0 + ox_min + hx;
+        const bool ok = hy < HH && (unsigned)iy < (unsigned)p.IH && (unsigned)ix < (unsigned)p.IW;
+        h_off[a] = ok ? (uint32_t)(((img * p.IH + iy) * p.IW + ix) * p.Cin + lane_c) * 2u : OOB_OFFSET;
+    }
+    const int bj = n0 + wave * 16 + lrow;                // this lane's filter row: one 16-row piece per wave
+    const uint32_t b_off = bj < p.Nout ? (uint32_t)(bj * BK + lane_c) * 2u : OOB_OFFSET;
+
+    // ---- cursors (all wave-uniform) -------------------------------------------
+    int ld_rs = 0, ld_cs = 0, ld_chunk = 0;              // step whose filter tile is fetched next
+    int cs = 0, chunk = 0;                               // step being multiplied (its row shift is compile-time)
+
+    auto issue_filter = [&](int slot) {
+        const int jr = flip_r ? 2 - ld_rs : ld_rs, js = flip_s ? 2 - ld_cs : ld_cs;
+        const uint32_t tile_b = (uint32_t)((ld_chunk * NT + jr * 3 + js) * p.Nout) * (BK * 2u);   // past the end: out of range
+        dma_load_16B(rsB, lds_addr(&sB[slot][0]) + wave * 16 * BK * 2, b_off != OOB_OFFSET ? b_off + tile_b : OOB_OFFSET);
+        if (++ld_rs == 3) {
+            ld_rs = 0;
+            if (++ld_cs == 3) { ld_cs = 0; ++ld_chunk; }
+        }
+    };
+    // piece `a_sel` of the halo image of chunk `ch` (zeros past the last chunk / in a ragged chunk)
+    auto issue_halo_piece = [&](int a_sel, int ch) {
+        uint32_t off = OOB_OFFSET;
+        const int c0 = ch * BK;
+#pragma unroll
+        for (int a = 0; a < AW; ++a)
+            if (a == a_sel && h_off[a] != OOB_OFFSET && lane_c < p.Cin - c0) off = h_off[a] + (uint32_t)c0 * 2u;
+        dma_load_16B(rsA, lds_addr(&sH[ch & 1][0]) + (wave + a_sel * NW) * 16 * BK * 2, off);
+    };
+    auto issue_spare = [&]() { dma_load_16B(rsA, lds_addr(sSpare) + wave * 16 * BK * 2, OOB_OFFSET); };
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // ---- fragment addressing ---------------------------------------------------
+    const int frow = lane & 31;
+    const int v0 = lane >> 5;                            // 16-byte slice of the first 16-deep half; the second is v0 + 2
+    int foff[2];                                         // filter: row frow of a 32-row tile, swizzled by row
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) foff[ks] = frow * BK + (((ks * 2 + v0) ^ p3_swz(frow)) << 3);
+    const int hbase = (wm * TM) * HW + frow;             // halo pixel of (first patch row of the wave, column frow), shift 0
+
+    u32x4_t fa[TM + 2][2], fb[2][TN];
+    // the six halo rows under the wave's four patch rows, at column shift cs
+    auto read_rows = [&]() {
+        const uint16_t *hal = &sH[chunk & 1][0];
+#pragma unroll
+        for (int r = 0; r < TM + 2; ++r) {
+            const int h = hbase + r * HW + cs;
+            const int e0 = h * BK + ((v0 ^ p3_swz(h)) << 3);
+            fa[r][0] = *reinterpret_cast<const u32x4_t *>(hal + e0);
+            fa[r][1] = *reinterpret_cast<const u32x4_t *>(hal + (e0 ^ 16));   // slice v0 + 2: flips bit 1 of the slice
+        }
+    };
+    auto read_filter = [&](int slot) {
+        const uint16_t *wb = &sB[slot][0] + wn * TN * 32 * BK;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[ks][j] = *reinterpret_cast<const u32x4_t *>(wb + j * 32 * BK + foff[ks]);
+    };
+    // Barrier that opens a read phase: this wave's loads for the step about to be read have
+    // landed (S - 2 later steps may be in flight) and its own LDS reads are complete.
+    auto sync_loaded = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto sync_phase = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Step k of a turn of six: ring slot k, row shift k % 3.
+    auto step = [&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        constexpr int u = k % 3;
+        sync_loaded();
+        if (u == 0) read_rows();
+        read_filter(k);
+        issue_filter((k + S - 1) % S);                   // the slot the previous step has finished with
+        const int q = cs * 3 + u;                        // step within the chunk
+        if (q < AW) issue_halo_piece(q, chunk + 1);
+        else issue_spare();
+        sync_phase();
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fa[i + u][s], fb[s][j], acc[i][j]);
+        if (u == 2 && ++cs == 3) { cs = 0; ++chunk; }
+    };
+
+    const int nk = nchunks * NT;
+    const int nturns = (nk + S - 1) / S;                 // whole turns of the ring; extra steps multiply zeros
+    // prologue: halo of chunk 0, then five filter tiles, each padded to PER_STEP loads
+#pragma unroll
+    for (int a = 0; a < AW; ++a) issue_halo_piece(a, 0);
+#pragma unroll
+    for (int k = 0; k < S - 1; ++k) { issue_filter(k); issue_spare(); }
+    const bool late_group = wave >= NW / 2;              // waves 4..7: the second wave on each SIMD
+    if (late_group) sync_loaded();
+    for (int turn = 0; turn < nturns; ++turn) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 5>{});
+    }
+    if (!late_group) sync_phase();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue ---------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int y = y0 + wm * TM + i;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int x = x0 + acc_row(v, lane);
+            if (y >= p.OH || x >= p.OW) continue;
+            const size_t row_off = ((size_t)(img * p.OH + y) * p.OW + x) * p.ldd;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
+            }
+        }
+    }
+}
+
+bool igemm_halo3x3_applicable(const IgemmArgs &a)
+{
+    const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
+    return dense && a.TR == 3 && a.TS == 3 && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0;
+}
+
+int64_t igemm_halo3x3_tiles(const IgemmArgs &a)
+{
+    return (int64_t)a.NB * ((a.OH + P3_PH - 1) / P3_PH) * ((a.OW + P3_PW - 1) / P3_PW) * ((a.Nout + P3_BN - 1) / P3_BN);
+}
+
+hipError_t launch_igemm_halo3x3(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
+{
+    const int64_t tiles = igemm_halo3x3_tiles(a);
+    if (!igemm_halo3x3_applicable(a) || tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)tiles), block(512);
+    if (is_bf16) hipLaunchKernelGGL(igemm_halo3x3_kernel<BF16>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(igemm_halo3x3_kernel<F16>, grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace dlk

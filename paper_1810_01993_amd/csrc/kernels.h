@@ -38,7 +38,10 @@ hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream
 
 // Halo-tile variant for stride-1 multi-tap filters.  a.B must point at the
 // blocked filter copy [chunk][tap][a.Nout][32] made by launch_filter_block.
-bool igemm_use_halo(const IgemmArgs &a);
+int igemm_halo_columns(const IgemmArgs &a);
+bool igemm_halo3x3_applicable(const IgemmArgs &a);
+int64_t igemm_halo3x3_tiles(const IgemmArgs &a);
+hipError_t launch_igemm_halo3x3(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 size_t igemm_blocked_filter_bytes(const IgemmArgs &a);
 hipError_t launch_igemm_halo(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 

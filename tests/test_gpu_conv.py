@@ -114,14 +114,17 @@ def test_big_tile_path(api):
     check_layer(api, L("bigtile", 2, 192, 288, 16, 256, 3, 3, 1, 1, 1), "f16", synth.seed_for(0, 501))
 
 
-# Shapes that take the halo-tile kernel (stride 1, several taps, >= 160 output
-# columns, >= 200 patches): ragged patches, ragged channel chunk, dilation 2,
-# a column remainder handed to the plain engine, both data types.
+# Shapes that take the halo-tile kernels (stride 1, several taps, >= 200
+# tiles): the 3x3 unit-dilation kernel and the general one; ragged patches,
+# ragged channel chunk, ragged column tile, dilation 2, a column remainder
+# handed to the plain engine, no padding, both data types.
 HALO = [
     (L("halo.ragged", 2, 150, 170, 40, 256, 3, 3, 1, 1, 1), "f16"),
     (L("halo.d2.n192", 1, 230, 250, 32, 192, 3, 3, 1, 2, 2), "bf16"),
     (L("halo.dgrad.c304", 1, 230, 250, 304, 32, 3, 3, 1, 1, 1), "f16"),
     (L("halo.5x5.nopad", 1, 240, 260, 16, 160, 5, 5, 1, 0, 1), "bf16"),
+    (L("halo.3x3.n224.c72", 1, 200, 333, 72, 224, 3, 3, 1, 1, 1), "bf16"),
+    (L("halo.3x3.nopad", 2, 130, 140, 48, 128, 3, 3, 1, 0, 1), "f16"),
 ]
 
 
