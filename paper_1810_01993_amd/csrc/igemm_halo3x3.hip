@@ -158,9 +158,12 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
+    // Barrier between a wave's read phase and its multiply phase.  The other group opens its
+    // read phase of the next step here, so this wave's loads for that step must have landed
+    // too (it has issued one more step since its last wait, hence the same count).
     auto sync_phase = [&]() {
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_barrier" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
     // Step k of a turn of six: ring slot k, row shift k % 3.
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fa[i + u][s], fb[s][j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fb[s][j], fa[i + u][s], acc[i][j]);   // rows = channels
         if (u == 2 && ++cs == 3) { cs = 0; ++chunk; }
     };
 
@@ -202,21 +205,53 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
         step(std::integral_constant<int, 5>{});
     }
     if (!late_group) sync_phase();
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // every wave's loads (the trailing ones deposit zeros) and LDS reads are over before LDS is reused
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     // ---- epilogue ---------------------------------------------------------------
+    // The filter rode in the first MFMA operand, so register v of lane l holds
+    // channel 8*(v/4) + 4*(l/32) + v%4 of pixel l%32: four consecutive
+    // channels per register quartet.  Each wave rounds its tile to 16 bits,
+    // parks it in a private LDS area as [pixel][64 channels] (two patch rows at
+    // a time, row pitch 136 bytes: conflict-free 8-byte writes) and writes it
+    // out as whole 128-byte rows, 16 bytes per lane.
+    constexpr int EP = 68;                               // staging pitch in 16-bit elements
+    static_assert(NW * 64 * EP <= 2 * HALO_ROWS * BK, "staging area must fit the halo buffers");
+    uint16_t *stg = &sH[0][0] + wave * 64 * EP;
+    const bool vec_ok = (p.ldd % 8 == 0) && (p.Nout % 8 == 0) && ((reinterpret_cast<uintptr_t>(p.D) & 15) == 0);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int y = y0 + wm * TM + i;
+    for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int x = x0 + acc_row(v, lane);
-            if (y >= p.OH || x >= p.OW) continue;
-            const size_t row_off = ((size_t)(img * p.OH + y) * p.OW + x) * p.ldd;
+        for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const floatx16_t &c = acc[2 * h + ii][j];
+                    u32x2_t pk;
+                    pk[0] = (uint32_t)T::from_float(c[4 * g]) | ((uint32_t)T::from_float(c[4 * g + 1]) << 16);
+                    pk[1] = (uint32_t)T::from_float(c[4 * g + 2]) | ((uint32_t)T::from_float(c[4 * g + 3]) << 16);
+                    const int px = ii * 32 + (lane & 31), ch = j * 32 + 8 * g + 4 * (lane >> 5);
+                    *reinterpret_cast<u32x2_t *>(stg + px * EP + ch) = pk;
+                }
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int px = it * 8 + (lane >> 3), c8 = (lane & 7) * 8;
+            const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(stg + px * EP + c8);
+            const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(stg + px * EP + c8 + 4);
+            const int y = y0 + wm * TM + 2 * h + (px >> 5), x = x0 + (px & 31);
+            const int col = n0 + wn * 64 + c8;
+            if (y >= p.OH || x >= p.OW || col >= p.Nout) continue;
+            uint16_t *dst = p.D + ((size_t)(img * p.OH + y) * p.OW + x) * p.ldd + col;
+            if (vec_ok) {
+                u32x4_t v4;
+                v4[0] = lo[0]; v4[1] = lo[1]; v4[2] = hi[0]; v4[3] = hi[1];
+                *reinterpret_cast<u32x4_t *>(dst) = v4;
+            } else {
+                const uint32_t w4[4] = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (col + e < p.Nout) dst[e] = (uint16_t)(w4[e >> 1] >> (16 * (e & 1)));
             }
         }
     }
