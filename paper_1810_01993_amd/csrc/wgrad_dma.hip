@@ -243,31 +243,62 @@ WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
         pl.splits = (int)((npix + pl.chunk - 1) / pl.chunk);
         return pl;
     }
-    int bm = 128, bn = 128;
-    int64_t target = 1024;                                   // workgroups wanted in flight overall
     const bool dma_ok = K % 8 == 0 && C % 8 == 0 && K >= 32 && RSC >= 64;
-    if (dma_ok && forced != -1) {
-        if (forced >= 0) pl.cfg = forced;
-        else if (K <= 64) pl.cfg = 2;
-        else if (K <= 128) pl.cfg = 3;
-        else pl.cfg = 0;
-        switch (pl.cfg) {
-            case 0: bm = 256; bn = 256; target = 512; break;
-            case 1: bm = 128; bn = 128; target = 1024; break;
-            case 2: bm = 64; bn = 256; target = 1024; break;
-            default: bm = 128; bn = 256; target = 768; break;
+    if (!dma_ok || forced == -1 || forced > 3) {
+        // register-transposing fallback kernel (128 x 128 tiles): about 1024 workgroups
+        const int64_t tiles = (int64_t)((K + 127) / 128) * ((RSC + 127) / 128);
+        int64_t s = (1024 + tiles - 1) / tiles;
+        const int64_t max_by_len = (npix + 127) / 128;       // at least four 32-pixel steps per slice
+        if (s > max_by_len) s = max_by_len;
+        if (s > 512) s = 512;
+        if (s < 1) s = 1;
+        int64_t chunk = (npix + s - 1) / s;
+        chunk = (chunk + 31) / 32 * 32;
+        pl.chunk = (int)chunk;
+        pl.splits = (int)((npix + chunk - 1) / chunk);
+        return pl;
+    }
+    // Direct-to-LDS kernel: pick the tile shape and the number of pixel slices by a small
+    // cost model.  The kernel gives all tiles of a slice to one XCD, so what counts is how
+    // many rounds of workgroups the busiest XCD (32 CUs) has to run: a slice count that
+    // leaves the last round almost empty costs a whole round.  Per round a workgroup spends
+    // its reduction steps plus a fixed start-up; the fp32 partial tiles are written and read
+    // back once per slice.  The constants are fitted to measured times on MI355X.
+    struct Shape { int bm, bn, per_cu; double us_per_step; };
+    static const Shape shapes[4] = {{256, 256, 1, 0.92}, {128, 128, 2, 0.55}, {64, 256, 2, 0.71}, {128, 256, 1, 0.88}};
+    static const int forced_target = [] {
+        const char *e = std::getenv("DLCONV_WGRAD_TARGET");   // tuning override: workgroups wanted, unset in normal use
+        return e ? std::atoi(e) : 0;
+    }();
+    const double outputs = (double)K * RSC;
+    double best = 1e300;
+    for (int cfg = 0; cfg < 4; ++cfg) {
+        if (forced >= 0 && cfg != forced) continue;
+        const Shape &sh = shapes[cfg];
+        const int64_t tiles = (int64_t)((K + sh.bm - 1) / sh.bm) * ((RSC + sh.bn - 1) / sh.bn);
+        const int64_t cap = 32 * sh.per_cu;                  // workgroups one XCD holds at a time
+        for (int cand = 0; cand < 67; ++cand) {
+            // 1, 2, 4 slices (fewer than XCDs), then 8, 16, ... 512: the same number on every XCD
+            int64_t s = cand < 3 ? (1 << cand) : 8 * (cand - 2);
+            if (forced_target > 0) s = (forced_target + tiles - 1) / tiles;
+            if (s > 512) break;
+            if (s > 1 && s * 128 > npix) break;              // at least four 32-pixel steps per slice
+            int64_t chunk = (npix + s - 1) / s;
+            chunk = (chunk + 31) / 32 * 32;
+            const int64_t splits = (npix + chunk - 1) / chunk;
+            const int64_t per_xcd = (splits + 7) / 8;
+            const int64_t rounds = (tiles * per_xcd + cap - 1) / cap;
+            const double reduce_us = (splits > 1 ? splits * outputs * 8.0 : outputs * 6.0) / 11.5e6;
+            const double est = 9.0 + rounds * (chunk / 32 + 7) * sh.us_per_step + reduce_us;
+            if (est < best) {
+                best = est;
+                pl.cfg = cfg;
+                pl.chunk = (int)chunk;
+                pl.splits = (int)splits;
+            }
+            if (forced_target > 0) break;
         }
     }
-    const int64_t tiles = (int64_t)((K + bm - 1) / bm) * ((RSC + bn - 1) / bn);
-    int64_t s = (target + tiles - 1) / tiles;
-    const int64_t max_by_len = (npix + 127) / 128;           // at least four 32-pixel steps per slice
-    if (s > max_by_len) s = max_by_len;
-    if (s > 512) s = 512;
-    if (s < 1) s = 1;
-    int64_t chunk = (npix + s - 1) / s;
-    chunk = (chunk + 31) / 32 * 32;
-    pl.chunk = (int)chunk;
-    pl.splits = (int)((npix + chunk - 1) / chunk);
     return pl;
 }
 
