@@ -271,16 +271,18 @@ static bool halo_takes(const IgemmArgs &a)
     return tiles >= 200;
 }
 
-// Leading output columns a halo-tile kernel takes (0 = none).  A trailing
-// remainder that would fill less than about two thirds of a column tile is
-// left to the plain engine.
+// Leading output columns a halo-tile kernel takes (0 = none).  The 3x3 kernel takes any
+// column count (it has a narrow variant for a short last tile); the general kernel leaves
+// a trailing remainder that would fill less than about two thirds of its 256-wide tile
+// to the plain engine.
 int igemm_halo_columns(const IgemmArgs &a)
 {
     if (!halo_mode()) return 0;
-    const int bn = use_3x3(a) ? 128 : HALO_BN, enough = use_3x3(a) ? 96 : 160;
-    const int rem = a.Nout % bn;
     IgemmArgs h = a;
-    if (rem != 0 && rem < enough) h.Nout = a.Nout - rem;
+    if (!use_3x3(a)) {
+        const int rem = a.Nout % HALO_BN;
+        if (rem != 0 && rem < 160) h.Nout = a.Nout - rem;
+    }
     return halo_takes(h) ? h.Nout : 0;
 }
 

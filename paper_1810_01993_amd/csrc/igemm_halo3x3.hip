@@ -39,11 +39,15 @@ constexpr int P3_HH = P3_PH + 2, P3_HW = P3_PW + 2;
 __device__ __forceinline__ int p3_swz(int row) { return (row >> 2) & 3; }
 }  // namespace
 
-template <class T>
-__global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
+// TN: 32-channel MFMA tiles per wave (2: the 128-channel tile; 1: a 64-channel tile for a narrow
+// last column tile).  The launch covers output channels [col0, col0 + p.Nout) of a blocked filter
+// copy that has bcols columns; p.D already points at column col0.
+template <class T, int TN>
+__global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, const int col0, const int bcols)
 {
-    constexpr int NW = 8, WN = 2, TM = 4, TN = 2;        // 4 x 2 waves, wave tile 4 patch rows x 64 channels
-    constexpr int HW = P3_HW, HH = P3_HH, BN = P3_BN;
+    constexpr int NW = 8, WN = 2, TM = 4;                // 4 x 2 waves, wave tile 4 patch rows x 32*TN channels
+    constexpr int HW = P3_HW, HH = P3_HH, BN = WN * TN * 32;
+    constexpr int BPIECES = BN / 16;                     // 16-row filter pieces per step: the first BPIECES waves fetch one each
     constexpr int NT = 9;
     constexpr int AW = 5;                                // halo pieces per wave: 5*8*16 = 640 >= 18*34 pixels
     constexpr int HALO_ROWS = AW * NW * 16;
@@ -74,7 +78,7 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
     const int y0 = ty * P3_PH, x0 = tx * P3_PW, n0 = tn * BN;
 
     const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
-    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)nchunks * NT * p.Nout * BK * 2u);
+    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)nchunks * NT * bcols * BK * 2u);
 
     // ---- what this lane fetches ---------------------------------------------
     const int lrow = lane >> 2;
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
         h_off[a] = ok ? (uint32_t)(((img * p.IH + iy) * p.IW + ix) * p.Cin + lane_c) * 2u : OOB_OFFSET;
     }
     const int bj = n0 + wave * 16 + lrow;                // this lane's filter row: one 16-row piece per wave
-    const uint32_t b_off = bj < p.Nout ? (uint32_t)(bj * BK + lane_c) * 2u : OOB_OFFSET;
+    const uint32_t b_off = (wave < BPIECES && bj < p.Nout) ? (uint32_t)((col0 + bj) * BK + lane_c) * 2u : OOB_OFFSET;
 
     // ---- cursors (all wave-uniform) -------------------------------------------
     int ld_rs = 0, ld_cs = 0, ld_chunk = 0;              // step whose filter tile is fetched next
@@ -98,8 +102,10 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
 
     auto issue_filter = [&](int slot) {
         const int jr = flip_r ? 2 - ld_rs : ld_rs, js = flip_s ? 2 - ld_cs : ld_cs;
-        const uint32_t tile_b = (uint32_t)((ld_chunk * NT + jr * 3 + js) * p.Nout) * (BK * 2u);   // past the end: out of range
-        dma_load_16B(rsB, lds_addr(&sB[slot][0]) + wave * 16 * BK * 2, b_off != OOB_OFFSET ? b_off + tile_b : OOB_OFFSET);
+        const uint32_t tile_b = (uint32_t)((ld_chunk * NT + jr * 3 + js) * bcols) * (BK * 2u);   // past the end: out of range
+        // a wave beyond the tile's pieces keeps the load count uniform with a stand-in (zeros into its spare area)
+        const uint32_t dst = wave < BPIECES ? lds_addr(&sB[slot][0]) + wave * 16 * BK * 2 : lds_addr(sSpare) + wave * 16 * BK * 2;
+        dma_load_16B(rsB, dst, b_off != OOB_OFFSET ? b_off + tile_b : OOB_OFFSET);
         if (++ld_rs == 3) {
             ld_rs = 0;
             if (++ld_cs == 3) { ld_cs = 0; ++ld_chunk; }
@@ -215,7 +221,9 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
     // parks it in a private LDS area as [pixel][64 channels] (two patch rows at
     // a time, row pitch 136 bytes: conflict-free 8-byte writes) and writes it
     // out as whole 128-byte rows, 16 bytes per lane.
-    constexpr int EP = 68;                               // staging pitch in 16-bit elements
+    constexpr int CH = TN * 32;                          // channels per wave
+    constexpr int EP = CH + 4;                           // staging pitch in 16-bit elements (8 bytes of padding)
+    constexpr int LPR = CH / 8;                          // lanes per pixel row when writing out
     static_assert(NW * 64 * EP <= 2 * HALO_ROWS * BK, "staging area must fit the halo buffers");
     uint16_t *stg = &sH[0][0] + wave * 64 * EP;
     const bool vec_ok = (p.ldd % 8 == 0) && (p.Nout % 8 == 0) && ((reinterpret_cast<uintptr_t>(p.D) & 15) == 0);
@@ -235,12 +243,12 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p)
                     *reinterpret_cast<u32x2_t *>(stg + px * EP + ch) = pk;
                 }
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int px = it * 8 + (lane >> 3), c8 = (lane & 7) * 8;
+        for (int it = 0; it < LPR; ++it) {               // 64 pixels x LPR lanes, 64 lanes at a time
+            const int px = it * (64 / LPR) + lane / LPR, c8 = (lane % LPR) * 8;
             const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(stg + px * EP + c8);
             const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(stg + px * EP + c8 + 4);
             const int y = y0 + wm * TM + 2 * h + (px >> 5), x = x0 + (px & 31);
-            const int col = n0 + wn * 64 + c8;
+            const int col = n0 + wn * CH + c8;
             if (y >= p.OH || x >= p.OW || col >= p.Nout) continue;
             uint16_t *dst = p.D + ((size_t)(img * p.OH + y) * p.OW + x) * p.ldd + col;
             if (vec_ok) {
@@ -263,18 +271,39 @@ bool igemm_halo3x3_applicable(const IgemmArgs &a)
     return dense && a.TR == 3 && a.TS == 3 && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0;
 }
 
-int64_t igemm_halo3x3_tiles(const IgemmArgs &a)
+static int64_t patches(const IgemmArgs &a)
 {
-    return (int64_t)a.NB * ((a.OH + P3_PH - 1) / P3_PH) * ((a.OW + P3_PW - 1) / P3_PW) * ((a.Nout + P3_BN - 1) / P3_BN);
+    return (int64_t)a.NB * ((a.OH + P3_PH - 1) / P3_PH) * ((a.OW + P3_PW - 1) / P3_PW);
 }
 
+int64_t igemm_halo3x3_tiles(const IgemmArgs &a) { return patches(a) * ((a.Nout + P3_BN - 1) / P3_BN); }
+
+// The output channels are cut into 128-wide column tiles; a last tile of at most 64
+// channels gets a launch of its own with the 64-wide kernel, which costs half as much.
 hipError_t launch_igemm_halo3x3(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
 {
-    const int64_t tiles = igemm_halo3x3_tiles(a);
-    if (!igemm_halo3x3_applicable(a) || tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)tiles), block(512);
-    if (is_bf16) hipLaunchKernelGGL(igemm_halo3x3_kernel<BF16>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(igemm_halo3x3_kernel<F16>, grid, block, 0, stream, a);
+    if (!igemm_halo3x3_applicable(a) || a.Nout <= 0) return hipErrorInvalidValue;
+    const int rem = a.Nout % P3_BN;
+    const int narrow = (rem > 0 && rem <= 64) ? rem : 0;
+    const int wide = a.Nout - narrow;
+    const int64_t tiles_wide = patches(a) * ((wide + P3_BN - 1) / P3_BN), tiles_narrow = narrow ? patches(a) : 0;
+    if (tiles_wide > 0x7fffffff || tiles_narrow > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 block(512);
+    if (wide > 0) {
+        IgemmArgs w = a;
+        w.Nout = wide;
+        if (is_bf16) hipLaunchKernelGGL((igemm_halo3x3_kernel<BF16, 2>), dim3((unsigned)tiles_wide), block, 0, stream, w, 0, a.Nout);
+        else hipLaunchKernelGGL((igemm_halo3x3_kernel<F16, 2>), dim3((unsigned)tiles_wide), block, 0, stream, w, 0, a.Nout);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (narrow > 0) {
+        IgemmArgs n = a;
+        n.Nout = narrow;
+        n.D = a.D + wide;
+        if (is_bf16) hipLaunchKernelGGL((igemm_halo3x3_kernel<BF16, 1>), dim3((unsigned)tiles_narrow), block, 0, stream, n, wide, a.Nout);
+        else hipLaunchKernelGGL((igemm_halo3x3_kernel<F16, 1>), dim3((unsigned)tiles_narrow), block, 0, stream, n, wide, a.Nout);
+    }
     return hipGetLastError();
 }
 

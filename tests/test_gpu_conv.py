@@ -125,6 +125,7 @@ HALO = [
     (L("halo.5x5.nopad", 1, 240, 260, 16, 160, 5, 5, 1, 0, 1), "bf16"),
     (L("halo.3x3.n224.c72", 1, 200, 333, 72, 224, 3, 3, 1, 1, 1), "bf16"),
     (L("halo.3x3.nopad", 2, 130, 140, 48, 128, 3, 3, 1, 0, 1), "f16"),
+    (L("halo.3x3.k192.narrow-tile", 1, 210, 300, 24, 192, 3, 3, 1, 1, 1), "f16"),
 ]
 
 
