@@ -45,9 +45,10 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     static_assert(TM >= 1 && TN >= 1, "wave tile too small");
     constexpr int IN_FLIGHT = (STAGES - 2) * (AIW + BIW);   // loads that may still be pending at the wait
 
-    // One array per ring slot.
-    __shared__ __align__(16) uint16_t sA0[BM * BK], sA1[BM * BK], sA2[BM * BK], sA3[BM * BK];
-    __shared__ __align__(16) uint16_t sB0[BN * BK], sB1[BN * BK], sB2[BN * BK], sB3[BN * BK];
+    // Ring slots of both operands in one array; the epilogue re-uses it as staging space.
+    __shared__ __align__(16) uint16_t lds[STAGES * (BM + BN) * BK];
+    uint16_t *const sA0 = lds, *const sA1 = lds + BM * BK, *const sA2 = lds + 2 * BM * BK, *const sA3 = lds + 3 * BM * BK;
+    uint16_t *const sB0 = lds + 4 * BM * BK, *const sB1 = sB0 + BN * BK, *const sB2 = sB0 + 2 * BN * BK, *const sB3 = sB0 + 3 * BN * BK;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fa[s][i], fb[s][j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = T::mfma(fb[s][j], fa[s][i], acc[i][j]);   // rows = output channels
     };
 
     // Wait until this wave's loads for the oldest pending step have landed,
@@ -208,18 +209,45 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
             wait_and_sync(); issue(sA1, sB1); mma(sA2, sB2);
             wait_and_sync(); issue(sA2, sB2); mma(sA3, sB3);
         }
-        // drain the (all-zero) loads issued past the end before the block retires its LDS
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    // every wave's loads (the trailing ones deposit zeros) and LDS reads are over before LDS is reused
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- epilogue: round once, 32 lanes write 32 consecutive channels -----
+    // ---- epilogue ---------------------------------------------------------------
+    // The filter rode in the first MFMA operand, so register v of lane l holds output
+    // channel 8*(v/4) + 4*(l/32) + v%4 of tile row l%32: four consecutive channels per
+    // register quartet.  Each wave rounds one 32-row slab of its tile at a time, parks it in a
+    // private LDS area as [row][channel] (pitch: the wave's channels + 8 bytes, conflict-free
+    // for the 8-byte writes) and writes it out 16 bytes per lane, whole rows of the wave's
+    // channel range at a time.
+    constexpr int CH = TN * 32;                          // channels per wave
+    constexpr int EP = CH + 4;                           // staging pitch in 16-bit elements
+    constexpr int LPR = CH / 8;                          // lanes per row when writing out
+    static_assert(NW * 32 * EP <= STAGES * (BM + BN) * BK, "staging area must fit the ring");
+    uint16_t *stg = lds + wave * 32 * EP;
     const bool dense = (p.osh == 1 && p.osw == 1 && p.FH == p.OH && p.FW == p.OW);
+    const bool vec_ok = (p.ldd % 8 == 0) && (p.Nout % 8 == 0) && ((reinterpret_cast<uintptr_t>(p.D) & 15) == 0);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = m0 + (wm * TM + i) * 32 + acc_row(v, lane);
-            if (m >= M) continue;
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const floatx16_t &c = acc[i][j];
+                u32x2_t pk;
+                pk[0] = (uint32_t)T::from_float(c[4 * g]) | ((uint32_t)T::from_float(c[4 * g + 1]) << 16);
+                pk[1] = (uint32_t)T::from_float(c[4 * g + 2]) | ((uint32_t)T::from_float(c[4 * g + 3]) << 16);
+                const int row = lane & 31, ch = j * 32 + 8 * g + 4 * (lane >> 5);
+                *reinterpret_cast<u32x2_t *>(stg + row * EP + ch) = pk;
+            }
+#pragma unroll
+        for (int it = 0; it < LPR / 2; ++it) {           // 32 rows x LPR lanes, 64 lanes at a time
+            const int row = it * (64 / LPR) + lane / LPR, c8 = (lane % LPR) * 8;
+            const u32x2_t lo = *reinterpret_cast<const u32x2_t *>(stg + row * EP + c8);
+            const u32x2_t hi = *reinterpret_cast<const u32x2_t *>(stg + row * EP + c8 + 4);
+            const int m = m0 + (wm * TM + i) * 32 + row;
+            const int col = n0 + wn * CH + c8;
+            if (m >= M || col >= p.Nout) continue;
             size_t row_off;
             if (dense) {
                 row_off = (size_t)m * p.ldd;
@@ -228,10 +256,16 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
                 const int oh = rem / p.OW, ow = rem - oh * p.OW;
                 row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
             }
+            uint16_t *dst = p.D + row_off + col;
+            if (vec_ok) {
+                u32x4_t v4;
+                v4[0] = lo[0]; v4[1] = lo[1]; v4[2] = hi[0]; v4[3] = hi[1];
+                *reinterpret_cast<u32x4_t *>(dst) = v4;
+            } else {
+                const uint32_t w4[4] = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
+                for (int e = 0; e < 8; ++e)
+                    if (col + e < p.Nout) dst[e] = (uint16_t)(w4[e >> 1] >> (16 * (e & 1)));
             }
         }
     }
