@@ -41,9 +41,12 @@ struct PixCursor {            // (n, p, q) of one output pixel, advanced without
 };
 
 // LDS image of a tile: row = pixel (BX channels = 2*BX bytes), and within a
-// row the 32-byte block b (16 channels) sits at block b ^ (pixel & 3): the
-// four pixel rows touched by one transpose read then use four different
-// 32-byte bank ranges.
+// row the 32-byte block b (16 channels) sits at block b ^ (2 * (pixel & 3))
+// (b ^ (pixel & 3) for rows of only four blocks).  Half a wave (the unit a
+// 64-bit LDS read serves per cycle) touches four pixel rows x two adjacent
+// blocks; rows are a multiple of the 256-byte bank width apart, and the rule
+// puts those eight 32-byte pieces on eight different bank ranges.
+__device__ __host__ constexpr int swz_shift(int BX) { return BX >= 128 ? 1 : 0; }
 template <class T, int BM, int BN, int WM, int WN, int STAGES>
 __global__ __launch_bounds__(WM *WN * 64) void wgrad_dma_kernel(const WgradArgs p)
 {
@@ -87,12 +90,12 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_dma_kernel(const WgradArgs 
     const int a_pchunk = lane % LPR_A;                      // physical 16-byte chunk within the row
     // pixel & 3 is the same for all of this lane's instructions (see static_asserts on NW / PPI)
     const int a_pix3 = ((wave * PPI_A) + a_prow) & 3;
-    const int a_ch = k0 + ((((a_pchunk >> 1) ^ a_pix3) << 1) | (a_pchunk & 1)) * 8;
+    const int a_ch = k0 + ((((a_pchunk >> 1) ^ (a_pix3 << swz_shift(BM))) << 1) | (a_pchunk & 1)) * 8;
     const bool a_ok = a_ch < p.K;
 
     const int b_prow = lane / LPR_B, b_pchunk = lane % LPR_B;
     const int b_pix3 = ((wave * PPI_B) + b_prow) & 3;
-    const int b_col = j0 + ((((b_pchunk >> 1) ^ b_pix3) << 1) | (b_pchunk & 1)) * 8;
+    const int b_col = j0 + ((((b_pchunk >> 1) ^ (b_pix3 << swz_shift(BN))) << 1) | (b_pchunk & 1)) * 8;
     const bool b_ok = b_col < RSC;
     const int b_tap = b_col / p.C, b_c = b_col - b_tap * p.C;
     const int b_r = b_tap / p.S, b_s = b_tap - b_r * p.S;
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_dma_kernel(const WgradArgs 
     // element offset of (pixel, 32-channel tile `ct`, this lane) in a [BK][BX] tile
     auto frag_off = [&](int BX, int pix, int ch_tile0) {
         const int ch = ch_tile0 + f_ch;
-        const int blk = (ch >> 4) ^ (pix & 3);
+        const int blk = (ch >> 4) ^ ((pix & 3) << swz_shift(BX));
         return pix * BX + blk * 16 + f_sub;
     };
     auto read_frag = [&](const uint16_t *tile, int BX, int ks, int ch_tile0) {
