@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: filter gradients of the small layers run on a second HIP stream beside the data-gradient chain")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "igemm_halo3x3_config5_traffic.txt"))
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference for HBM byte counters")
@@ -77,8 +79,10 @@ class LayerState:
         self.y = torch.empty_like(self.dy)
         self.dx = torch.empty_like(self.x)
         self.dw = torch.empty_like(self.w)
-        nb = max(api.dl_conv_workspace_bytes(self.desc, p) for p in (0, 1, 2))
+        nb = max(api.dl_conv_workspace_bytes(self.desc, p) for p in (0, 1))
         self.ws = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
+        # the filter gradient may run beside the data gradient: its own workspace
+        self.ws_w = torch.empty(max(api.dl_conv_workspace_bytes(self.desc, 2), 16), dtype=torch.uint8, device="cuda")
 
 
 def cpu_baseline():
@@ -152,6 +156,8 @@ def main():
     timed = {(i, which) for i, st in enumerate(net) for (name, which) in DOMINANT_CALLS if st.layer.name == name}
     timed.add(("loss", "loss"))
 
+    side_stream = torch.cuda.Stream() if args.streams == 2 else None      # default priority
+
     def step(events=None):
         def rec(key):
             if events is not None and (args.table or (key[0], key[1]) in timed):
@@ -165,14 +171,36 @@ def main():
         rec(("loss", "loss", 0))
         api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n_pix, loss=loss, dlogits=dlogits, workspace=ce_ws)
         rec(("loss", "loss", 1))
+        # Backward.  In the network, layer i's filter gradient and data gradient both consume
+        # dy_i, which the layer above has produced before either starts.  With two streams the
+        # data-gradient chain stays on the main stream and the filter gradients of the small
+        # layers (tens of microseconds each, too short to fill the chip alone) follow on the
+        # second stream, each gated by an event recorded on the main stream at the point where
+        # its dy exists; the large decoder and logits layers, which fill the chip by
+        # themselves, keep both passes on the main stream.
         for i in range(len(net) - 1, -1, -1):
             st = net[i]
+            side = side_stream is not None and st.layer.flops() < 1e12
+            if side:
+                ready = torch.cuda.Event()
+                ready.record()
+                side_stream.wait_event(ready)
             rec((i, "dgrad", 0))
             api.conv2d_bwd_data(st.desc, st.dy, st.w, dx=st.dx, workspace=st.ws)
             rec((i, "dgrad", 1))
-            rec((i, "wgrad", 0))
-            api.conv2d_bwd_filter(st.desc, st.x, st.dy, dw=st.dw, workspace=st.ws)
-            rec((i, "wgrad", 1))
+            if side:
+                with torch.cuda.stream(side_stream):
+                    rec((i, "wgrad", 0))
+                    api.conv2d_bwd_filter(st.desc, st.x, st.dy, dw=st.dw, workspace=st.ws_w)
+                    rec((i, "wgrad", 1))
+            else:
+                rec((i, "wgrad", 0))
+                api.conv2d_bwd_filter(st.desc, st.x, st.dy, dw=st.dw, workspace=st.ws_w)
+                rec((i, "wgrad", 1))
+        if side_stream is not None:
+            done = torch.cuda.Event()
+            done.record(side_stream)
+            torch.cuda.current_stream().wait_event(done)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
@@ -246,6 +274,7 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, fp16 in / fp32 accumulate",
+                   "streams": args.streams,
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
                    "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9},
