@@ -160,8 +160,18 @@ size_t dgrad_workspace(const dl_conv_desc *d, const Geometry &g)
     return total;
 }
 
+bool use_wgrad3x3(const dl_conv_desc *d)
+{
+    return dlk::wgrad3x3_applicable(d->N, d->H, d->W, d->C, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+                                    d->dil_h, d->dil_w);
+}
+
 dlk::WgradPlan wgrad_plan(const dl_conv_desc *d, const Geometry &g)
 {
+    if (use_wgrad3x3(d)) {
+        const dlk::Wgrad3x3Plan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
+        return dlk::WgradPlan{-3, p3.slices, 0};
+    }
     const bool thin = dlk::thin_wgrad_applicable(d->K, d->C, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w);
     return dlk::wgrad_make_plan((int64_t)d->N * g.P * g.Q, d->K, d->C, d->R * d->S * d->C, thin);
 }
@@ -307,7 +317,16 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w; a.dh = d->dil_h; a.dw = d->dil_w;
     a.splits = plan.splits;
     a.chunk = plan.chunk;
-    hipError_t e = plan.cfg >= 0    ? dlk::launch_wgrad_dma(a, d->dtype == DL_BF16, plan.cfg, stream)
+    hipError_t e;
+    if (plan.cfg == -3) {
+        const dlk::Wgrad3x3Plan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
+        dlk::Wgrad3x3Args w{};
+        w.x = a.x; w.dy = a.dy; w.partial = a.partial;
+        w.N = d->N; w.H = d->H; w.W = d->W; w.C = d->C; w.K = d->K;
+        w.slices = p3.slices; w.rs = p3.rs; w.xs = p3.xs;
+        e = dlk::launch_wgrad3x3(w, d->dtype == DL_BF16, stream);
+    } else
+    e = plan.cfg >= 0    ? dlk::launch_wgrad_dma(a, d->dtype == DL_BF16, plan.cfg, stream)
                    : plan.cfg == -2 ? dlk::launch_thin_wgrad(a, d->dtype == DL_BF16, stream)
                                     : dlk::launch_wgrad(a, d->dtype == DL_BF16, stream);
     if (e != hipSuccess) return DL_ERR_LAUNCH;

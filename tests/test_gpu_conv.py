@@ -134,6 +134,14 @@ def test_halo_tile_kernel(api, layer, dtype):
     check_layer(api, layer, dtype, synth.seed_for(0, 600 + len(layer.name)), x_kind="normal", n_samples=8192)
 
 
+def test_wgrad_3x3_fused_taps(api):
+    # large-image 3x3 filter gradient (all taps per workgroup): ragged strip, ragged channel block, ragged k
+    check_layer(api, L("wgrad3x3.ragged", 1, 330, 1000, 40, 72, 3, 3, 1, 1, 1), "bf16", synth.seed_for(0, 700),
+                x_kind="normal", passes=("wgrad",))
+    check_layer(api, L("wgrad3x3.k264", 2, 400, 416, 32, 264, 3, 3, 1, 1, 1), "f16", synth.seed_for(0, 701),
+                x_kind="normal", passes=("wgrad",))
+
+
 def test_fp32_filter_gradient(api):
     layer = L("dw32", 2, 19, 23, 24, 40, 3, 3, 1, 1, 1)
     (x32, xb), _, (dy32, dyb) = U.conv_inputs(layer, "bf16", 77, "normal")
