@@ -75,10 +75,12 @@ struct FilterSrc { const uint16_t *src; int64_t base, sj, sr, ss, sc; };
 
 int halo_columns(const dlk::IgemmArgs &a) { return dlk::igemm_halo_columns(a); }
 
+// Scratch one implicit GEMM needs: the blocked filter copy of a halo kernel, or the fp32 partial
+// sums of a split reduction of the plain engine (never both).
 size_t igemm_scratch_bytes(const dlk::IgemmArgs &a)
 {
     const int cols = halo_columns(a);
-    if (!cols) return 0;
+    if (!cols) return align_up(dlk::igemm_split_bytes(a), 256);
     dlk::IgemmArgs h = a;
     h.Nout = cols;
     return align_up(dlk::igemm_blocked_filter_bytes(h), 256);
@@ -88,7 +90,11 @@ size_t igemm_scratch_bytes(const dlk::IgemmArgs &a)
 hipError_t run_igemm(const dlk::IgemmArgs &a, bool bf16, const FilterSrc &fs, uint16_t *scratch, hipStream_t stream)
 {
     const int cols = halo_columns(a);
-    if (!cols) return dlk::launch_igemm(a, bf16, stream);
+    if (!cols) {
+        dlk::IgemmArgs g = a;
+        g.part = dlk::igemm_split_bytes(a) ? reinterpret_cast<float *>(scratch) : nullptr;
+        return dlk::launch_igemm(g, bf16, stream);
+    }
     dlk::FilterBlockArgs f{};
     f.src = fs.src; f.dst = scratch;
     f.base = fs.base; f.sj = fs.sj; f.sr = fs.sr; f.ss = fs.ss; f.sc = fs.sc;

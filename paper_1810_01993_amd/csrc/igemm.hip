@@ -300,6 +300,72 @@ static int forced_cfg()
     return v;
 }
 
+static bool choose_c_outer(const IgemmArgs &a)
+{
+    static const int force_order = [] {
+        const char *e = std::getenv("DLCONV_C_OUTER");
+        return e ? std::atoi(e) : -1;
+    }();
+    // channel-major order needs the tap mask to fit 64 bits and no chunk that is mostly padding
+    const bool cm_ok = a.TR * a.TS <= 64;
+    return cm_ok && (force_order >= 0 ? force_order != 0 : (a.Cin % 32 == 0 || a.Cin >= 128));
+}
+
+// Split of the reduction for GEMMs with few output pixels and a very long reduction (the
+// ASPP 3x3 layers' forward pass: 6912 x 256 outputs, reduction 18432).  With tiles small enough
+// to give every CU one, such a GEMM is bound by the L2 -> LDS traffic of its operand tiles
+// (12 KB per 0.5 MFLOP step of a 128 x 64 tile: 1.5 GB, 12 TB/s).  Instead the 256 x 256 tile
+// (a third of the traffic per FLOP) is used and ranges of channel chunks run side by side;
+// an ordered reduce adds their fp32 partial sums.  Returns the number of ranges (1: no split)
+// and the chunks per range.
+static int choose_ksplits(const IgemmArgs &a, int *chunks_per_split)
+{
+    static const int mode = [] {
+        const char *e = std::getenv("DLCONV_KSPLIT");         // tuning override: 0 = never
+        return e ? std::atoi(e) : 1;
+    }();
+    *chunks_per_split = 0;
+    if (!mode || forced_cfg() >= 0 || a.Cin % 8 != 0 || !choose_c_outer(a)) return 1;
+    const bool dense = a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW && a.ldd == a.Nout;
+    if (!dense || a.Nout < 256 || a.Nout % 256 != 0) return 1;
+    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    const int64_t tiles = ((M + 255) / 256) * (a.Nout / 256);
+    const int nchunks = (a.Cin + BK - 1) / BK;
+    const int64_t steps = (int64_t)nchunks * a.TR * a.TS;
+    if (steps < 256 || tiles > 64 || M * a.Nout > (4 << 20)) return 1;
+    int64_t ks = 256 / tiles;                                 // one workgroup per CU
+    if (ks > 8) ks = 8;
+    if (ks > nchunks) ks = nchunks;
+    if (ks < 2) return 1;
+    const int cps = (int)((nchunks + ks - 1) / ks);
+    *chunks_per_split = cps;
+    return (nchunks + cps - 1) / cps;
+}
+
+size_t igemm_split_bytes(const IgemmArgs &a)
+{
+    int cps;
+    const int ks = choose_ksplits(a, &cps);
+    return ks > 1 ? (size_t)ks * a.NB * a.OH * a.OW * a.Nout * sizeof(float) : 0;
+}
+
+// Tile configuration of the direct-to-LDS engine for this GEMM (100 + its cfg), or the forced one.
+static int choose_cfg(const IgemmArgs &a)
+{
+    int cfg = forced_cfg();
+    if (cfg >= 0) return cfg;
+    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    // Largest tile that still yields enough workgroups for 256 CUs; tiles
+    // wider than the output-channel count (rounded up to 64) are not considered.
+    const int nmax = (a.Nout + 63) / 64 * 64;
+    auto blocks = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((a.Nout + bn - 1) / bn); };
+    if (nmax <= 32 || a.Nout <= 32) return 104;                     // 64 x 32
+    if (nmax >= 256 && blocks(256, 256) >= 200) return 100;         // 256 x 256
+    if (nmax >= 128 && blocks(128, 128) >= 400) return 102;         // 128 x 128
+    if (blocks(128, 64) >= 200) return 103;                         // 128 x 64
+    return 108;                                                     // 64 x 64
+}
+
 template <class T>
 static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 {
@@ -311,27 +377,23 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
         hipLaunchKernelGGL(igemm_scalar_kernel<T>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
         return hipGetLastError();
     }
-    int cfg = forced_cfg();
-    if (cfg < 0) {
-        // Largest tile that still yields enough workgroups for 256 CUs; tiles
-        // wider than the output-channel count (rounded up to 64) are not considered.
-        const int nmax = (a.Nout + 63) / 64 * 64;
-        auto blocks = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((a.Nout + bn - 1) / bn); };
-        if (nmax <= 32 || a.Nout <= 32) cfg = 104;                     // 64 x 32
-        else if (nmax >= 256 && blocks(256, 256) >= 200) cfg = 100;    // 256 x 256
-        else if (nmax >= 128 && blocks(128, 128) >= 400) cfg = 102;    // 128 x 128
-        else if (blocks(128, 64) >= 200) cfg = 103;                    // 128 x 64
-        else cfg = 108;                                                // 64 x 64
-    }
+    const int cfg = choose_cfg(a);
     if (cfg >= 100) {
         IgemmArgs b = a;
-        static const int force_order = [] {
-            const char *e = std::getenv("DLCONV_C_OUTER");
-            return e ? std::atoi(e) : -1;
-        }();
-        // channel-major order needs the tap mask to fit 64 bits and no chunk that is mostly padding
-        const bool cm_ok = a.TR * a.TS <= 64;
-        b.c_outer = cm_ok && (force_order >= 0 ? force_order != 0 : (a.Cin % 32 == 0 || a.Cin >= 128));
+        b.c_outer = choose_c_outer(a);
+        b.ksplits = 1;
+        b.split_chunks = 0;
+        if (a.part) {
+            int cps;
+            const int ks = choose_ksplits(a, &cps);
+            if (ks > 1) {
+                b.ksplits = ks;
+                b.split_chunks = cps;
+                hipError_t e = launch_igemm_dma(b, std::is_same<T, BF16>::value, 0, stream);      // 256 x 256 tiles
+                if (e != hipSuccess) return e;
+                return launch_splitk_reduce(a.part, ks, M * a.Nout, a.D, std::is_same<T, BF16>::value ? 1 : 0, stream);
+            }
+        }
         // A ragged last column tile of the widest configuration (e.g. 304 = 256 + 48 output
         // channels) would run mostly empty: give the remainder to a narrower tile instead.
         const int rem = a.Nout % 256;

@@ -105,7 +105,14 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
 
     // ---- reduction cursor ---------------------------------------------------
     // channel-major: (t, jr, js, c0) are wave-uniform; tap-major: (kk, c, js, jr) per lane
-    int t = 0, jr = 0, js = 0, c0 = 0;
+    // channels [c_first, c_end) of the reduction belong to this workgroup (all of them unless the reduction is split)
+    const int split = blockIdx.y;
+    int c_first = 0, c_end = p.Cin;
+    if (CMAJOR && p.ksplits > 1) {
+        c_first = split * p.split_chunks * BK;
+        c_end = min(p.Cin, c_first + p.split_chunks * BK);
+    }
+    int t = 0, jr = 0, js = 0, c0 = c_first;
     int kk = vec * 8, c = 0;
     if constexpr (!CMAJOR) { c = kk % p.Cin; js = (kk / p.Cin) % p.TS; jr = (kk / p.Cin) / p.TS; }
     const int lane_c = vec * 8;
@@ -115,7 +122,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
         if constexpr (CMAJOR) {
             const uint32_t tap_a = (uint32_t)(((jr * p.dth) * p.IW + js * p.dtw) * p.Cin + c0) * 2u;   // uniform
             const uint32_t tap_b = (uint32_t)(t * p.Cin + c0) * 2u;                                    // uniform
-            const bool cin = lane_c < p.Cin - c0;        // false only in a ragged last chunk / past the end
+            const bool cin = lane_c < c_end - c0;        // false only in a ragged last chunk / past the end
 #pragma unroll
             for (int i = 0; i < AIW; ++i) {
                 const uint32_t word = t < 32 ? a_mask_lo[i] : a_mask_hi[i];
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
 
     // The step count is rounded up to a whole turn of the ring (the extra
     // steps load and multiply zeros) so that the unrolled loop has one exit.
-    const int nk = CMAJOR ? ((p.Cin + BK - 1) / BK) * NT : (Kred + BK - 1) / BK;
+    const int nk = CMAJOR ? ((c_end - c_first + BK - 1) / BK) * NT : (Kred + BK - 1) / BK;
     const int nturns = (nk + STAGES - 1) / STAGES;
     if (nk > 0) {
         issue(sA0, sB0);
@@ -220,6 +227,32 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     // private LDS area as [row][channel] (pitch: the wave's channels + 8 bytes, conflict-free
     // for the 8-byte writes) and writes it out 16 bytes per lane, whole rows of the wave's
     // channel range at a time.
+    if (CMAJOR && p.ksplits > 1) {
+        // split reduction: fp32 partial sums, four consecutive channels per store
+        float *out = p.part + (size_t)split * M * p.Nout;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + (wm * TM + i) * 32 + (lane & 31);
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = n0 + (wn * TN + j) * 32 + 8 * g + 4 * (lane >> 5);
+                    float *dst = out + (size_t)m * p.Nout + col;
+                    if (col + 3 < p.Nout && (p.Nout & 3) == 0) {
+                        floatx4_t v4;
+                        v4[0] = acc[i][j][4 * g]; v4[1] = acc[i][j][4 * g + 1]; v4[2] = acc[i][j][4 * g + 2]; v4[3] = acc[i][j][4 * g + 3];
+                        *reinterpret_cast<floatx4_t *>(dst) = v4;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < p.Nout) dst[e] = acc[i][j][4 * g + e];
+                    }
+                }
+        }
+        return;
+    }
     constexpr int CH = TN * 32;                          // channels per wave
     constexpr int EP = CH + 4;                           // staging pitch in 16-bit elements
     constexpr int LPR = CH / 8;                          // lanes per row when writing out
@@ -277,7 +310,7 @@ static hipError_t launch_dma_cfg(const IgemmArgs &a, hipStream_t stream)
     const int64_t M = (int64_t)a.NB * a.OH * a.OW;
     const int64_t tiles = ((M + BM - 1) / BM) * ((a.Nout + BN - 1) / BN);
     if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)tiles), block(WM * WN * 64);
+    const dim3 grid((unsigned)tiles, (unsigned)(a.c_outer && a.ksplits > 1 ? a.ksplits : 1)), block(WM * WN * 64);
     if (a.c_outer)
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, a);
     else

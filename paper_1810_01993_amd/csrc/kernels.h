@@ -28,7 +28,15 @@ struct IgemmArgs {
     int32_t th0, dth, tw0, dtw;
     int32_t FH, FW, osh, osw, ooh, oow, ldd;
     int32_t c_outer;            // direct-to-LDS engine only: channel-major reduction order
+    // Split reduction (direct-to-LDS engine, channel-major order, dense output with ldd == Nout):
+    // with ksplits > 1 the 32-channel chunks are cut into ksplits ranges of split_chunks chunks,
+    // range z (grid.y) writes fp32 partial sums to part[z][m][j] and an ordered reduce follows.
+    int32_t ksplits, split_chunks;
+    float *part;                // scratch for the partial sums, or null: never split
 };
+
+// Bytes of partial-sum scratch launch_igemm would use for this GEMM if a.part were set (0: it would not split).
+size_t igemm_split_bytes(const IgemmArgs &a);
 
 // is_bf16 selects the MFMA flavour and the output rounding.
 hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream);

@@ -100,6 +100,9 @@ SMALL = [
     L("nopad.3x3", 1, 9, 9, 8, 8, 3, 3, 1, 0, 1),
     L("single-pixel-out", 1, 3, 3, 8, 8, 3, 3, 1, 0, 1),
     L("wide.n-tiles", 1, 16, 24, 32, 328, 3, 3, 1, 1, 1),
+    # few output pixels, long reduction: the reduction is split over workgroups (ragged last chunk, ragged columns)
+    L("ksplit.3x3.c1000", 1, 20, 24, 1000, 256, 3, 3, 1, 1, 1),
+    L("ksplit.1x1.c8200", 2, 12, 20, 8200, 256, 1, 1, 1, 0, 1),
 ]
 
 
