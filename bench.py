@@ -176,11 +176,11 @@ def main():
         # data-gradient chain stays on the main stream and the filter gradients of the small
         # layers (tens of microseconds each, too short to fill the chip alone) follow on the
         # second stream, each gated by an event recorded on the main stream at the point where
-        # its dy exists; the large decoder and logits layers, which fill the chip by
-        # themselves, keep both passes on the main stream.
+        # its dy exists; the large decoder layers and the bandwidth-bound full-resolution logits
+        # layer, which fill the chip by themselves, keep both passes on the main stream.
         for i in range(len(net) - 1, -1, -1):
             st = net[i]
-            side = side_stream is not None and st.layer.flops() < 1e12
+            side = side_stream is not None and st.layer.flops() < 1e12 and st.layer.bytes_fwd() < 2e8
             if side:
                 ready = torch.cuda.Event()
                 ready.record()
