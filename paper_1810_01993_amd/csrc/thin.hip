@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
             }
             out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
         }
-        *reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j) = out;
+        // streamed store: the output (0.9 GB for the logits layer) is far larger than the caches
+        __builtin_nontemporal_store(out, reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j));
     }
 }
 
