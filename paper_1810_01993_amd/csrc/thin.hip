@@ -75,10 +75,14 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
 //   partial[b][k][c] = sum over workgroup b's pixels of dy[pix][k] * x[pix][c].
 // A workgroup is (C/8 channel groups) x (256 / (C/8) pixel lanes); every thread
 // keeps K x 8 running sums, the pixel lanes are then added in a fixed order.
+// The workgroup's slice of dy is staged in LDS as fp32, 512 pixels at a time, so
+// that the inner loop issues one 16-byte global load per pixel and nothing else.
 template <class T>
 __global__ __launch_bounds__(256) void thin_wgrad_kernel(const WgradArgs p)
 {
+    constexpr int SUB = 512;                             // pixels of dy staged at a time
     __shared__ float red[256 * 8];                       // 8 sums per thread, reused for each k
+    __shared__ float sdy[SUB * THIN_MAX];
     const int groups = p.C / 8;                          // <= 256
     const int lanes = 256 / groups;                      // pixel lanes per workgroup
     const int g = threadIdx.x % groups, pl = threadIdx.x / groups;
@@ -89,23 +93,33 @@ __global__ __launch_bounds__(256) void thin_wgrad_kernel(const WgradArgs p)
     for (int k = 0; k < THIN_MAX; ++k)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[k][e] = 0.f;
-    if (pl < lanes) {
+    for (int sub = pix_begin; sub < pix_end; sub += SUB) {
+        const int sub_end = min(pix_end, sub + SUB);
+        __syncthreads();                                 // the previous part of dy is no longer read
+        for (int i = threadIdx.x; i < (sub_end - sub) * p.K; i += 256) {
+            const int px = i / p.K, k = i - px * p.K;
+            sdy[px * THIN_MAX + k] = T::to_float(p.dy[(size_t)sub * p.K + i]);
+        }
+        __syncthreads();
+        if (pl < lanes) {
 #pragma unroll 4
-        for (int pix = pix_begin + pl; pix < pix_end; pix += lanes) {
-            const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8);
-            float xf[8];
+            for (int pix = sub + pl; pix < sub_end; pix += lanes) {
+                const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8);
+                float xf[8];
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                xf[2 * d] = T::to_float((uint16_t)(xv[d] & 0xffffu));
-                xf[2 * d + 1] = T::to_float((uint16_t)(xv[d] >> 16));
-            }
-#pragma unroll
-            for (int k = 0; k < THIN_MAX; ++k)
-                if (k < p.K) {
-                    const float gk = T::to_float(p.dy[(size_t)pix * p.K + k]);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[k][e] += gk * xf[e];
+                for (int d = 0; d < 4; ++d) {
+                    xf[2 * d] = T::to_float((uint16_t)(xv[d] & 0xffffu));
+                    xf[2 * d + 1] = T::to_float((uint16_t)(xv[d] >> 16));
                 }
+                const float *gd = sdy + (pix - sub) * THIN_MAX;
+#pragma unroll
+                for (int k = 0; k < THIN_MAX; ++k)
+                    if (k < p.K) {
+                        const float gk = gd[k];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[k][e] += gk * xf[e];
+                    }
+            }
         }
     }
     float *out = p.partial + (size_t)blockIdx.x * p.K * p.C;
