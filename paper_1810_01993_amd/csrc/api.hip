@@ -284,7 +284,17 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
             a.D = static_cast<uint16_t *>(dx);
             a.B = static_cast<const uint16_t *>(w);     // never read when there are no taps
             const bool all_halo = c.has_taps && halo_columns(a) == a.Nout;
-            if (c.has_taps && !all_halo) {
+            const int64_t SC = (int64_t)d->S * d->C;
+            // the plain engine can take the filter as it lies in memory (reduction-major for this GEMM)
+            const bool direct = c.has_taps && halo_columns(a) == 0 && dlk::igemm_accepts_transposed_b(a);
+            if (direct) {
+                a.b_transposed = 1;
+                a.b_base = (int32_t)(c.th.r0 * SC + (int64_t)c.tw.r0 * d->C);
+                a.b_sr = (int32_t)(c.th.rstep * SC);
+                a.b_ss = (int32_t)((int64_t)c.tw.rstep * d->C);
+                a.b_ldk = (int32_t)((int64_t)d->R * SC);
+                a.b_elems = (int32_t)g.w_elems;
+            } else if (c.has_taps && !all_halo) {
                 dlk::FilterRelayoutArgs f{};
                 f.w = static_cast<const uint16_t *>(w);
                 f.wt = wt;
@@ -294,7 +304,6 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
                 if (dlk::launch_filter_relayout(f, stream) != hipSuccess) return DL_ERR_LAUNCH;
                 a.B = wt;
             }
-            const int64_t SC = (int64_t)d->S * d->C;
             const FilterSrc fs{static_cast<const uint16_t *>(w), c.th.r0 * SC + (int64_t)c.tw.r0 * d->C, 1,
                                c.th.rstep * SC, (int64_t)c.tw.rstep * d->C, (int64_t)d->R * SC};
             if (run_igemm(a, bf16, fs, blk, stream) != hipSuccess) return DL_ERR_LAUNCH;

@@ -366,6 +366,16 @@ static int choose_cfg(const IgemmArgs &a)
     return 108;                                                     // 64 x 64
 }
 
+bool igemm_accepts_transposed_b(const IgemmArgs &a)
+{
+    static const int mode = [] {
+        const char *e = std::getenv("DLCONV_BT");             // tuning override: 0 = never
+        return e ? std::atoi(e) : 1;
+    }();
+    return mode && a.Cin % 8 == 0 && a.Nout % 8 == 0 && a.Nout >= 32 && !(forced_cfg() < 0 && thin_rows_applicable(a)) && choose_cfg(a) >= 100 &&
+           choose_c_outer(a);
+}
+
 template <class T>
 static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 {
@@ -401,7 +411,8 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
             IgemmArgs lo = b, hi = b;
             lo.Nout = a.Nout - rem;
             hi.Nout = rem;
-            hi.B = a.B + (size_t)lo.Nout * a.TR * a.TS * a.Cin;
+            if (a.b_transposed) hi.b_base = a.b_base + lo.Nout;
+            else hi.B = a.B + (size_t)lo.Nout * a.TR * a.TS * a.Cin;
             hi.D = a.D + lo.Nout;
             hipError_t e = launch_igemm_dma(lo, std::is_same<T, BF16>::value, 0, stream);
             if (e != hipSuccess) return e;

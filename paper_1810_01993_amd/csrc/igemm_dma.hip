@@ -34,9 +34,16 @@ namespace dlk {
 // 2-way conflict of an 8-row rule, four times an unswizzled 64-byte pitch.)
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
-template <class T, int BM, int BN, int WM, int WN, bool CMAJOR>
+typedef short bt_s16x4_t __attribute__((ext_vector_type(4)));
+
+// BT: the filter operand is given reduction-major (see IgemmArgs::b_transposed); channel-major order only.
+// Its tile is deposited as it lies in memory, [32 reduction channels][BN columns], 32-byte blocks of a
+// row XOR-swizzled with the row index, and the MFMA fragments (8 consecutive reduction channels of one
+// column per lane) come from ds_read_b64_tr_b16, as in the filter-gradient kernels.
+template <class T, int BM, int BN, int WM, int WN, bool CMAJOR, bool BT = false>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs p)
 {
+    static_assert(!BT || CMAJOR, "a reduction-major filter needs the channel-major order");
     constexpr int NW = WM * WN;
     constexpr int STAGES = 4;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -61,7 +68,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
     const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
-    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)p.Nout * Kred * 2u);
+    const i32x4_t rsB = make_rsrc_words(p.B, BT ? (uint32_t)p.b_elems * 2u : (uint32_t)p.Nout * Kred * 2u);
 
     // ---- what this lane fetches: row (16*inst + lane/4), logical slice vec --
     const int lrow = lane >> 2;                          // row within a 16-row load
@@ -102,6 +109,17 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
         b_ok[i] = j < p.Nout;
         b_off[i] = ((uint32_t)j * (uint32_t)Kred + vec * 8) * 2u;
     }
+    // reduction-major filter: a load covers RPI_B reduction rows of BN columns (LPR_B lanes of 16 bytes each);
+    // load `inst` = wave + i*NW of a step holds rows inst*RPI_B .. +RPI_B-1, so row & 3 does not depend on i
+    constexpr int LPR_B = BN / 8, RPI_B = 64 / LPR_B;
+    constexpr int BT_SHIFT = BN >= 128 ? 1 : 0;          // rows of >= 8 blocks: spread 4 rows x 2 blocks over 8 bank ranges
+    static_assert(!BT || (NW * RPI_B) % 4 == 0, "swizzle must not depend on the load index");
+    const int bt_row = lane / LPR_B;                     // row within a load
+    const int bt_row3 = (wave * RPI_B + bt_row) & 3;
+    const int bt_pc = lane % LPR_B;                      // physical 16-byte chunk within the row
+    const int bt_blk = BN >= 64 ? ((bt_pc >> 1) ^ (bt_row3 << BT_SHIFT)) : (bt_pc >> 1);
+    const int bt_col = n0 + ((bt_blk << 1) | (bt_pc & 1)) * 8;
+    const bool bt_ok = bt_col < p.Nout;
 
     // ---- reduction cursor ---------------------------------------------------
     // channel-major: (t, jr, js, c0) are wave-uniform; tap-major: (kk, c, js, jr) per lane
@@ -129,10 +147,20 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
                 const bool ok = cin && ((word >> (t & 31)) & 1u);
                 dma_load_16B(rsA, lds_addr(sa) + (wave + i * NW) * 16 * BK * 2, ok ? a_off[i] + tap_a : OOB_OFFSET);
             }
+            if constexpr (BT) {
+                const uint32_t tap_bt = (uint32_t)(p.b_base + jr * p.b_sr + js * p.b_ss + bt_col);     // per lane (column)
 #pragma unroll
-            for (int i = 0; i < BIW; ++i)
-                dma_load_16B(rsB, lds_addr(sb) + (wave + i * NW) * 16 * BK * 2,
-                             (cin && b_ok[i]) ? b_off[i] + tap_b : OOB_OFFSET);
+                for (int i = 0; i < BIW; ++i) {
+                    const int k = c0 + (wave + i * NW) * RPI_B + bt_row;
+                    dma_load_16B(rsB, lds_addr(sb) + (wave + i * NW) * 1024,
+                                 (bt_ok && k < c_end) ? (tap_bt + (uint32_t)k * (uint32_t)p.b_ldk) * 2u : OOB_OFFSET);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < BIW; ++i)
+                    dma_load_16B(rsB, lds_addr(sb) + (wave + i * NW) * 16 * BK * 2,
+                                 (cin && b_ok[i]) ? b_off[i] + tap_b : OOB_OFFSET);
+            }
             ++t;
             if (++js == p.TS) { js = 0; ++jr; }
             if (t == NT) { t = 0; jr = 0; js = 0; c0 += BK; }
@@ -176,12 +204,32 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
 
     // MFMAs of one slot (two 16-deep slices); the fragments of both slices are
     // requested from LDS before the first MFMA is issued.
+    // transpose-read addressing of a [32][BN] tile: lane = 16*g + q points at reduction row
+    // 8*(g>>1) + 4*half + q/4 (+ 16*ks) and columns 16*(g&1) + 4*(q%4)..+3 of a 32-column MFMA tile
+    const int tg = lane >> 4, tq = lane & 15;
+    const int t_row = 8 * (tg >> 1) + (tq >> 2);
+    const int t_sw = BN >= 64 ? ((t_row & 3) << BT_SHIFT) : 0;        // same for row + 4 and row + 16
+    const int t_sub = 4 * (tq & 3), t_blk = tg & 1;
     auto load_frags = [&](u32x4_t (&a)[TM], u32x4_t (&b)[TN], const uint16_t *sa, const uint16_t *sb, int ks) {
-        const uint16_t *wa = sa + wm * TM * 32 * BK + foff[ks], *wb = sb + wn * TN * 32 * BK + foff[ks];
+        const uint16_t *wa = sa + wm * TM * 32 * BK + foff[ks];
 #pragma unroll
         for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const u32x4_t *>(wa + i * 32 * BK);
+        if constexpr (BT) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4_t *>(wb + j * 32 * BK);
+            for (int j = 0; j < TN; ++j) {
+                const int blk = ((wn * TN + j) * 2 + t_blk) ^ t_sw;
+                const uint16_t *lo = sb + (16 * ks + t_row) * BN + blk * 16 + t_sub;
+                const bt_s16x4_t l4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((bt_s16x4_t __attribute__((address_space(3))) *)lo);
+                const bt_s16x4_t h4 =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((bt_s16x4_t __attribute__((address_space(3))) *)(lo + 4 * BN));
+                const u32x2_t l2 = __builtin_bit_cast(u32x2_t, l4), h2 = __builtin_bit_cast(u32x2_t, h4);
+                b[j][0] = l2[0]; b[j][1] = l2[1]; b[j][2] = h2[0]; b[j][3] = h2[1];
+            }
+        } else {
+            const uint16_t *wb = sb + wn * TN * 32 * BK + foff[ks];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4_t *>(wb + j * 32 * BK);
+        }
     };
     auto mma = [&](const uint16_t *sa, const uint16_t *sb) {
         u32x4_t fa[2][TM], fb[2][TN];
@@ -311,7 +359,10 @@ static hipError_t launch_dma_cfg(const IgemmArgs &a, hipStream_t stream)
     const int64_t tiles = ((M + BM - 1) / BM) * ((a.Nout + BN - 1) / BN);
     if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles, (unsigned)(a.c_outer && a.ksplits > 1 ? a.ksplits : 1)), block(WM * WN * 64);
-    if (a.c_outer)
+    if (a.b_transposed) {
+        if (!a.c_outer || a.Nout % 8 != 0) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true, true>), grid, block, 0, stream, a);
+    } else if (a.c_outer)
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, a);
     else
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, a);

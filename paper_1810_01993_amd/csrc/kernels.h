@@ -33,7 +33,18 @@ struct IgemmArgs {
     // range z (grid.y) writes fp32 partial sums to part[z][m][j] and an ordered reduce follows.
     int32_t ksplits, split_chunks;
     float *part;                // scratch for the partial sums, or null: never split
+    // Filter given reduction-major (direct-to-LDS engine, channel-major order, Nout % 8 == 0): with
+    // b_transposed != 0 element (column j, tap (jr, js), reduction channel c) of the filter operand is
+    // B[b_base + j + jr*b_sr + js*b_ss + c*b_ldk], i.e. contiguous along the columns -- how the data
+    // gradient finds it in the [K][R][S][C] filter.  Tiles are then deposited [channel][column] and the
+    // fragments come from LDS transpose reads, so no re-laid-out copy is needed.
+    int32_t b_transposed;
+    int32_t b_base, b_sr, b_ss, b_ldk;
+    int32_t b_elems;            // elements of the tensor B points into (bounds of the loads)
 };
+
+// Would launch_igemm accept this GEMM with a reduction-major filter (b_transposed)?
+bool igemm_accepts_transposed_b(const IgemmArgs &a);
 
 // Bytes of partial-sum scratch launch_igemm would use for this GEMM if a.part were set (0: it would not split).
 size_t igemm_split_bytes(const IgemmArgs &a);
