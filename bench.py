@@ -42,8 +42,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: filter gradients of the small layers run on a second HIP stream beside the data-gradient chain")
+    ap.add_argument("--streams", type=int, default=3, choices=(1, 2, 3, 4),
+                    help="2-4: filter gradients of the small layers run on 1-3 more HIP streams beside the "
+                         "data-gradient chain")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "igemm_halo3x3_config5_traffic.txt"))
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference for HBM byte counters")
@@ -156,7 +157,7 @@ def main():
     timed = {(i, which) for i, st in enumerate(net) for (name, which) in DOMINANT_CALLS if st.layer.name == name}
     timed.add(("loss", "loss"))
 
-    side_stream = torch.cuda.Stream() if args.streams == 2 else None      # default priority
+    side_streams = [torch.cuda.Stream() for _ in range(args.streams - 1)]   # default priority
 
     def step(events=None):
         def rec(key):
@@ -172,16 +173,17 @@ def main():
         api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n_pix, loss=loss, dlogits=dlogits, workspace=ce_ws)
         rec(("loss", "loss", 1))
         # Backward.  In the network, layer i's filter gradient and data gradient both consume
-        # dy_i, which the layer above has produced before either starts.  With two streams the
+        # dy_i, which the layer above has produced before either starts.  With several streams the
         # data-gradient chain stays on the main stream and the filter gradients of the small
         # layers (tens of microseconds each, too short to fill the chip alone) follow on the
-        # second stream, each gated by an event recorded on the main stream at the point where
+        # side streams in turn (they are independent of each other), each gated by an event recorded on the main stream at the point where
         # its dy exists; the large decoder layers and the bandwidth-bound full-resolution logits
         # layer, which fill the chip by themselves, keep both passes on the main stream.
         for i in range(len(net) - 1, -1, -1):
             st = net[i]
-            side = side_stream is not None and st.layer.flops() < 1e12 and st.layer.bytes_fwd() < 2e8
+            side = bool(side_streams) and st.layer.flops() < 1e12 and st.layer.bytes_fwd() < 2e8
             if side:
+                side_stream = side_streams[i % len(side_streams)]
                 ready = torch.cuda.Event()
                 ready.record()
                 side_stream.wait_event(ready)
@@ -197,9 +199,9 @@ def main():
                 rec((i, "wgrad", 0))
                 api.conv2d_bwd_filter(st.desc, st.x, st.dy, dw=st.dw, workspace=st.ws_w)
                 rec((i, "wgrad", 1))
-        if side_stream is not None:
+        for ss in side_streams:
             done = torch.cuda.Event()
-            done.record(side_stream)
+            done.record(ss)
             torch.cuda.current_stream().wait_event(done)
 
     if args.calibrate_copy:
