@@ -219,6 +219,35 @@ def test_config5_full_size_layers(api, layer):
     torch.cuda.empty_cache()
 
 
+def test_decoder_layer_bf16_full_size(api):
+    """The dominant layer at its benchmark size in bfloat16: 3x3 halo kernel (forward, data gradient) and the
+    fused-tap filter-gradient kernel, sampled outputs."""
+    layer = [l for l in CFG5 if l.name == "dec.3x3.256-256"][0]
+    check_layer(api, layer, "bf16", synth.seed_for(5, 777), n_samples=16384)
+    torch.cuda.empty_cache()
+
+
+def test_determinism_of_the_large_layer_kernels(api):
+    """Two runs of the halo-tile, fused-tap filter-gradient and split-reduction paths give identical bits."""
+    cases = [L("det.halo3x3", 2, 150, 170, 40, 256, 3, 3, 1, 1, 1),          # 3x3 halo kernel, ragged everything
+             L("det.wgrad3x3", 1, 330, 1000, 40, 72, 3, 3, 1, 1, 1),         # fused-tap filter gradient
+             L("det.ksplit", 1, 20, 24, 1000, 256, 3, 3, 1, 1, 1)]           # split reduction + ordered reduce
+    for layer in cases:
+        (_, xb), (_, wb), (_, dyb) = U.conv_inputs(layer, "f16", 4242, "normal")
+        desc = api.desc_from_layer(layer, "f16")
+        xd, wd, dyd = U.to_device(xb, "f16"), U.to_device(wb, "f16"), U.to_device(dyb, "f16")
+        outs = []
+        for _ in range(2):
+            _say(f"[case] {layer.name} determinism run")
+            y = api.conv2d_fwd(desc, xd, wd)
+            dx = api.conv2d_bwd_data(desc, dyd, wd)
+            dw = api.conv2d_bwd_filter(desc, xd, dyd)
+            torch.cuda.synchronize()
+            outs.append((y.clone(), dx.clone(), dw.clone()))
+        for a, b in zip(outs[0], outs[1]):
+            assert torch.equal(a, b), f"{layer.name}: results differ between two identical runs"
+
+
 # ---- host-forceable errors on a GPU box --------------------------------------
 def test_argument_errors(api):
     layer = L("err", 1, 8, 8, 8, 8, 3, 3, 1, 1, 1)
