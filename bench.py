@@ -38,8 +38,8 @@ DOMINANT_CALLS = (("dec.3x3.304-256", "fwd"), ("dec.3x3.256-256", "fwd"), ("dec.
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
     ap.add_argument("--streams", type=int, default=3, choices=(1, 2, 3, 4),
