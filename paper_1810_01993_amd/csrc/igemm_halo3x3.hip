@@ -166,10 +166,11 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
     };
     // Barrier between a wave's read phase and its multiply phase.  The other group opens its
     // read phase of the next step here, so this wave's loads for that step must have landed
-    // too (it has issued one more step since its last wait, hence the same count).
+    // too (it has issued one more step since its last wait, hence the same count), and its own LDS
+    // reads must be complete, because after this barrier the other group refills the slot just read.
     auto sync_phase = [&]() {
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
     // Step k of a turn of six: ring slot k, row shift k % 3.

@@ -161,10 +161,11 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
         __builtin_amdgcn_sched_barrier(0);
     };
     // The other group opens its read phase of the next step here, so this wave's loads for that
-    // step must have landed too (it has issued one more step since its last wait: same count).
+    // step must have landed too (it has issued one more step since its last wait: same count), and
+    // its own LDS reads must be complete: after this barrier the other group refills the slot just read.
     auto sync_phase = [&]() {
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
     // Step k of a turn of six: ring slot k; the new dy row goes into register set k % 3, the rows
