@@ -111,6 +111,33 @@ def cpu_baseline():
             "sample": f"fwd+dgrad+wgrad of a {rows}x1152 slab (1 image) of dec.3x3.256-256, fp64, {dt:.1f} s"}
 
 
+def loss_hbm_resident(api, torch, mult=64):
+    """The loss kernel on mult x the step's pixel count (1.47 GB of traffic at 64x): the step's own 23 MB
+    fit the last-level caches and take two kernel launches, so bandwidth is judged on this size."""
+    n = 2 * 768 * 1152 * mult
+    logits = torch.randn((n, 3), device="cuda", dtype=torch.float16)
+    labels = (torch.rand(n, device="cuda") < 0.02).to(torch.uint8)
+    cw = torch.tensor([1.0, 7.67, 31.6], dtype=torch.float32, device="cuda")
+    dl = torch.empty_like(logits)
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(api.dl_ce_workspace_bytes(n), 16), dtype=torch.uint8, device="cuda")
+    run = lambda: api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n, loss=loss, dlogits=dl, workspace=ws)
+    run()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            run()
+        b.record()
+        torch.cuda.synchronize()
+        ts.append(a.elapsed_time(b) / 10)
+    ms = float(np.median(ts))
+    gbs = 13 * n / (ms * 1e-3) / 1e9
+    return {"n_pixels": n, "ms": ms, "gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+
+
 def read_traffic(path):
     """HBM bytes per launch of the dominant kernel, from the committed
     rocprofv3 counter summary (a 'bytes_per_launch = <number>' line)."""
@@ -235,6 +262,8 @@ def main():
                 times.setdefault((who, which), []).append(opened[(who, which)].elapsed_time(e))
     med = {k: float(np.median(v)) for k, v in times.items()}
 
+    loss_big = loss_hbm_resident(api, torch)
+
     step_flops = layers.total_flops(table, passes=3)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -279,7 +308,8 @@ def main():
                    "streams": args.streams,
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
-                   "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9},
+                   "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9,
+                   "loss_hbm_resident": loss_big},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": read_traffic(args.traffic_file),
                      "kernel": "igemm_halo3x3_kernel<F16, 2>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
