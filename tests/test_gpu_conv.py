@@ -112,6 +112,38 @@ def test_small_shapes(api, layer, dtype):
     check_layer(api, layer, dtype, synth.seed_for(0, 7 * SMALL.index(layer)), x_kind="normal")
 
 
+def _random_layers(seed, count):
+    """Seeded random layer shapes: filter sizes 1..7, strides 1..3, dilations 1..6, paddings 0..half the
+    dilated filter, channel counts with and without the 8- and 32-alignment the fast paths want."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        R = rng.choice([1, 1, 3, 3, 3, 5, 7])
+        S = R if rng.random() < 0.8 else rng.choice([1, 3])
+        st = rng.choice([1, 1, 1, 2, 2, 3])
+        dil = rng.choice([1, 1, 2, 3, 6])
+        pad = rng.choice([0, dil * (R // 2), dil * (R // 2), 1, 2])
+        C = rng.choice([3, 8, 16, 24, 32, 40, 64, 72, 128, 136, 256, 304, 520])
+        K = rng.choice([3, 5, 8, 16, 32, 48, 64, 72, 128, 160, 256, 264, 304])
+        N, H, W = rng.choice([1, 2]), rng.randint(6, 70), rng.randint(6, 90)
+        if rng.random() < 0.2:                   # some maps large enough for the halo-tile kernels
+            H, W, C, K = rng.randint(150, 260), rng.randint(150, 300), min(C, 72), min(K, 264)
+        layer = L(f"rand{len(out)}.{H}x{W}x{C}-{K}.{R}x{S}.s{st}p{pad}d{dil}", N, H, W, C, K, R, S, st, pad, dil)
+        if layer.P >= 1 and layer.Q >= 1:
+            out.append((layer, rng.choice(["f16", "bf16"])))
+    return out
+
+
+RANDOM = _random_layers(20181001, 48)
+
+
+@pytest.mark.parametrize("layer,dtype", RANDOM, ids=[l.name for l, _ in RANDOM])
+def test_random_shapes(api, layer, dtype):
+    check_layer(api, layer, dtype, synth.seed_for(0, 900 + RANDOM.index((layer, dtype))), x_kind="normal",
+                n_samples=3000)
+
+
 def test_big_tile_path(api):
     # enough 256-row tiles that the wide configuration is selected; full oracle
     check_layer(api, L("bigtile", 2, 192, 288, 16, 256, 3, 3, 1, 1, 1), "f16", synth.seed_for(0, 501))
