@@ -2,13 +2,12 @@
 // re-laid-out filter, the data gradient).
 //
 // GEMM view: M = N*OH*OW output pixels, N = output channels, reduction over
-// (tap, input channel).  The im2col matrix is never materialised: each
-// 16-byte load of 8 consecutive input channels computes its own source pixel
-// from (output pixel, tap), which is where stride, padding and dilation
-// enter.  Padding pixels and ragged tile edges are fetched as out-of-range
-// buffer loads, which return zero without a branch.  Tiles are staged
-// global -> registers -> LDS: two register sets keep the loads two reduction
-// steps ahead of the MFMAs, two LDS buffers need one barrier per step.
+// (tap, input channel).  The im2col matrix is never materialised: every load
+// computes its own source pixel from (output pixel, tap), which is where
+// stride, padding and dilation enter.  This file holds the host-side choice of
+// kernel and tile for one implicit GEMM, the element-wise kernel for channel
+// counts that are not a multiple of 8, and the filter re-layout for data
+// gradients that cannot read the filter in place.
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -19,158 +18,8 @@
 namespace dlk {
 
 // ===========================================================================
-// Vector kernel: Cin % 8 == 0, so every 8-element slice of the reduction index
-// stays inside one tap and is one aligned 16-byte load.
-// ===========================================================================
-template <class T, int BM, int BN, int BKT, int WM, int WN, int MIN_WAVES>
-__global__ __launch_bounds__(WM *WN * 64, MIN_WAVES) void igemm_vec_kernel(const IgemmArgs p)
-{
-    constexpr int NT = WM * WN * 64;
-    constexpr int PITCH = BKT + 8;
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int VPR = BKT / 8;                         // 16-byte vectors per tile row
-    constexpr int RPP = NT / VPR;                        // tile rows covered by one pass of all threads
-    constexpr int PA = BM / RPP, PB = (BN + RPP - 1) / RPP;
-    constexpr bool B_PARTIAL = BN % RPP != 0;            // narrow filter tile: only rows < BN exist
-    static_assert(BM % RPP == 0 && TM >= 1 && TN >= 1, "tile / thread-count mismatch");
-
-    extern __shared__ __align__(16) uint16_t lds[];
-    uint16_t *sA = lds;                                  // [2][BM][PITCH]
-    uint16_t *sB = lds + 2 * BM * PITCH;                 // [2][BN][PITCH]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-
-    const int M = p.NB * p.OH * p.OW;
-    const int Kred = p.TR * p.TS * p.Cin;
-    const int tiles_n = (p.Nout + BN - 1) / BN;
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
-
-    const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
-    const __amdgpu_buffer_rsrc_t rsB = make_rsrc(p.B, (uint32_t)p.Nout * Kred * 2u);
-
-    // ---- per-thread load coordinates: fixed rows, fixed 8-element column --
-    const int vec = tid % VPR, row0 = tid / VPR;
-    int a_base[PA], a_ih[PA], a_iw[PA];                  // element offset of tap (0,0), its pixel coordinates
-#pragma unroll
-    for (int i = 0; i < PA; ++i) {
-        const int m = m0 + row0 + i * RPP;
-        if (m < M) {
-            const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
-            const int oh = rem / p.OW, ow = rem - oh * p.OW;
-            a_ih[i] = oh * p.sh + p.th0;
-            a_iw[i] = ow * p.sw + p.tw0;
-            a_base[i] = ((n * p.IH + a_ih[i]) * p.IW + a_iw[i]) * p.Cin;
-        } else {
-            a_base[i] = 0;
-            a_ih[i] = -(1 << 28);                        // fails every bounds test
-            a_iw[i] = 0;
-        }
-    }
-    uint32_t b_off[PB];
-#pragma unroll
-    for (int i = 0; i < PB; ++i) {
-        const int j = n0 + row0 + i * RPP;
-        const bool ok = j < p.Nout && (!B_PARTIAL || row0 + i * RPP < BN);
-        b_off[i] = ok ? (uint32_t)j * (uint32_t)Kred * 2u : OOB_OFFSET;
-    }
-    // reduction index of this thread's slice: kk = (jr*TS + js)*Cin + c
-    int kk = vec * 8;
-    int c = kk % p.Cin, js = (kk / p.Cin) % p.TS, jr = (kk / p.Cin) / p.TS;
-
-    auto load_tiles = [&](u32x4_t (&ra)[PA], u32x4_t (&rb)[PB]) {
-        const bool kin = kk < Kred;
-        const int dh = jr * p.dth, dw = js * p.dtw;
-        const int tap_off = (dh * p.IW + dw) * p.Cin + c;
-#pragma unroll
-        for (int i = 0; i < PA; ++i) {
-            const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
-            const bool ok = kin && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
-            ra[i] = buffer_load_16B(rsA, ok ? (uint32_t)(a_base[i] + tap_off) * 2u : OOB_OFFSET);
-        }
-#pragma unroll
-        for (int i = 0; i < PB; ++i)
-            rb[i] = buffer_load_16B(rsB, (kin && b_off[i] != OOB_OFFSET) ? b_off[i] + (uint32_t)kk * 2u : OOB_OFFSET);
-        // step this thread's slice to the next BKT-deep block
-        kk += BKT;
-        c += BKT;
-        while (c >= p.Cin) {
-            c -= p.Cin;
-            if (++js == p.TS) { js = 0; ++jr; }
-        }
-    };
-    auto store_tiles = [&](int buf, const u32x4_t (&ra)[PA], const u32x4_t (&rb)[PB]) {
-        uint16_t *da = sA + buf * BM * PITCH + row0 * PITCH + vec * 8;
-        uint16_t *db = sB + buf * BN * PITCH + row0 * PITCH + vec * 8;
-#pragma unroll
-        for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4_t *>(da + i * RPP * PITCH) = ra[i];
-#pragma unroll
-        for (int i = 0; i < PB; ++i)
-            if (!B_PARTIAL || row0 + i * RPP < BN) *reinterpret_cast<u32x4_t *>(db + i * RPP * PITCH) = rb[i];
-    };
-    auto mma = [&](int buf, floatx16_t (&acc)[TM][TN]) {
-        mma_step<T, TM, TN, BKT>(sA + buf * BM * PITCH + wm * TM * 32 * PITCH,
-                                 sB + buf * BN * PITCH + wn * TN * 32 * PITCH, lane, acc);
-    };
-
-    floatx16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int nk = (Kred + BKT - 1) / BKT;
-    if (nk > 0) {
-        // register set 0 holds even steps, set 1 odd steps; LDS buffer = step & 1
-        u32x4_t ra0[PA], rb0[PB], ra1[PA], rb1[PB];
-        load_tiles(ra0, rb0);
-        if (nk > 1) load_tiles(ra1, rb1);
-        store_tiles(0, ra0, rb0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; kt += 2) {
-            if (kt + 2 < nk) load_tiles(ra0, rb0);
-            mma(0, acc);
-            if (kt + 1 < nk) store_tiles(1, ra1, rb1);
-            __syncthreads();
-            if (kt + 1 >= nk) break;
-            if (kt + 3 < nk) load_tiles(ra1, rb1);
-            mma(1, acc);
-            if (kt + 2 < nk) store_tiles(0, ra0, rb0);
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue: round once, 32 lanes write 32 consecutive channels -----
-    const bool dense = (p.osh == 1 && p.osw == 1 && p.FH == p.OH && p.FW == p.OW);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = m0 + (wm * TM + i) * 32 + acc_row(v, lane);
-            if (m >= M) continue;
-            size_t row_off;
-            if (dense) {
-                row_off = (size_t)m * p.ldd;
-            } else {
-                const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
-                const int oh = rem / p.OW, ow = rem - oh * p.OW;
-                row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
-            }
-        }
-    }
-}
-
-// ===========================================================================
 // Scalar kernel: any channel count; elements are fetched one by one.  Used
-// only when Cin is not a multiple of 8 (e.g. the 3-channel logits gradient).
+// only when Cin is not a multiple of 8.
 // ===========================================================================
 template <class T>
 __global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
@@ -269,26 +118,6 @@ __global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
 // ===========================================================================
 // Host side: tile selection and launch
 // ===========================================================================
-template <class T, int BM, int BN, int BKT, int WM, int WN, int MIN_WAVES>
-static hipError_t launch_vec(const IgemmArgs &a, hipStream_t stream)
-{
-    auto kern = igemm_vec_kernel<T, BM, BN, BKT, WM, WN, MIN_WAVES>;
-    constexpr size_t lds = size_t(2) * (BM + BN) * (BKT + 8) * sizeof(uint16_t);
-    static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS");
-    static bool attr_set = false;                       // raising the LDS limit is idempotent
-    if (lds > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
-    const int64_t tiles = ((M + BM - 1) / BM) * ((a.Nout + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(WM * WN * 64), lds, stream, a);
-    return hipGetLastError();
-}
-
 // Tuning override: DLCONV_IGEMM_CFG=<n> forces tile configuration n for every
 // vector-path launch (used by the tile sweeps; unset in normal use).
 static int forced_cfg()
@@ -420,13 +249,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
         }
         return launch_igemm_dma(b, std::is_same<T, BF16>::value, cfg - 100, stream);
     }
-    switch (cfg) {
-        case 0: return launch_vec<T, 128, 32, 32, 4, 1, 2>(a, stream);
-        case 1: return launch_vec<T, 128, 64, 32, 2, 2, 2>(a, stream);
-        case 2: return launch_vec<T, 128, 128, 32, 2, 2, 2>(a, stream);
-        case 3: return launch_vec<T, 128, 128, 64, 2, 2, 2>(a, stream);
-        default: return hipErrorInvalidValue;
-    }
+    return hipErrorInvalidValue;                         // only the direct-to-LDS configurations (100 + n) exist
 }
 
 hipError_t launch_igemm(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
