@@ -279,14 +279,15 @@ def main():
     loss_ms = med[("loss", "loss")]
 
     if args.table:
-        print(f"{'layer':28s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%peak':>6s} {'GB/s(min)':>10s}", file=sys.stderr)
+        print(f"{'layer':28s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s}",
+              file=sys.stderr)
         for i, st in enumerate(net):
             for which in ("fwd", "dgrad", "wgrad"):
                 ms = med[(i, which)]
                 tf = st.layer.flops() / (ms * 1e-3) / 1e12
                 gbs = st.layer.bytes_fwd() / (ms * 1e-3) / 1e9
-                print(f"{st.layer.name:28s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f}",
-                      file=sys.stderr)
+                print(f"{st.layer.name:28s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
+                      f"{100 * gbs / HBM_PEAK_GBS:6.1f}", file=sys.stderr)
         print(f"loss: {loss_ms:.4f} ms  ({13 * n_pix / (loss_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)", file=sys.stderr)
         print(f"sum of per-call medians: conv {conv_ms:.3f} ms, loss {loss_ms:.4f} ms; wall {ms_per_step:.3f} ms/step",
               file=sys.stderr)
