@@ -21,6 +21,12 @@ struct F16 {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
                                                       __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
     }
+    // 16x16 output tile, 32-deep: lane l supplies row (column) l%16, reduction elements 8*(l/16)..+7;
+    // register v of lane l of the result holds row 4*(l/16) + v, column l%16
+    static __device__ __forceinline__ floatx4_t mfma16(u32x4_t a, u32x4_t b, floatx4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
     static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
         return __builtin_bit_cast(uint16_t, (_Float16)f);
     }
@@ -32,6 +38,10 @@ struct F16 {
 struct BF16 {
     static __device__ __forceinline__ floatx16_t mfma(u32x4_t a, u32x4_t b, floatx16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ floatx4_t mfma16(u32x4_t a, u32x4_t b, floatx4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                        __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
     static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
