@@ -27,6 +27,14 @@ struct F16 {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                       __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
     }
+    // The same product accumulating in place (result registers = addend registers).  The builtin
+    // leaves that choice to the register allocator, which in kernels with dozens of 4-register
+    // accumulators moves them about and runs out of registers.  The compiler does not see an MFMA
+    // here: the accumulator must not be touched by anything but further mfma16_acc calls until
+    // mfma_acc_settle() has run.
+    static __device__ __forceinline__ void mfma16_acc(floatx4_t &c, u32x4_t a, u32x4_t b) {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    }
     static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
         return __builtin_bit_cast(uint16_t, (_Float16)f);
     }
@@ -44,6 +52,9 @@ struct BF16 {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                        __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
+    static __device__ __forceinline__ void mfma16_acc(floatx4_t &c, u32x4_t a, u32x4_t b) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    }
     static __device__ __forceinline__ uint16_t from_float(float f) {       // nearest even
         uint32_t u = __builtin_bit_cast(uint32_t, f);
         if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // quiet NaN
@@ -54,6 +65,14 @@ struct BF16 {
         return __builtin_bit_cast(float, (uint32_t)h << 16);
     }
 };
+
+// Between the last mfma16_acc and the first other use of its accumulators: the result of an
+// 8-pass MFMA may be read by other instruction classes only 11 or more issue slots later, a gap
+// the compiler keeps for its own MFMAs and cannot keep for inline assembly.
+__device__ __forceinline__ void mfma_acc_settle()
+{
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
 
 // LDS tiles are [rows][BKT] 16-bit elements (BKT = 32 or 64) with the row
 // pitch padded by 8 elements (16 bytes): pitch/16 is then odd, so the 16-byte

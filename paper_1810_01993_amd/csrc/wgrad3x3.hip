@@ -15,12 +15,14 @@
 //   i.e. the x fragments of a row serve three taps with the dy fragments of
 //   three consecutive rows, which stay in registers from step to step.
 //
-// Per step that is 18.2 KB from L2 and 8 fragments from LDS for 18 MFMAs per
-// wave, against 32 KB and 12 fragments for 16 MFMAs in the general kernel.
+// Per step that is 18.2 KB from L2 and 8 fragments from LDS for 36 MFMAs of
+// 16x16x32 per wave (the 32 pixels of the row are one reduction block; this
+// MFMA shape draws less power per flop than 32x32x16, and the chip is
+// power-limited), against 32 KB and 12 fragments in the general kernel.
 // Both operands lie in memory with the reduction index (the pixel) as the slow
-// axis; they are deposited as they lie, [pixel][channel], by
-// `buffer_load_dwordx4 ... lds`, and the MFMA fragments (8 consecutive pixels of
-// one channel per lane) come from the LDS transpose read ds_read_b64_tr_b16.
+// axis; they are deposited pixel-major by `buffer_load_dwordx4 ... lds`, and the
+// MFMA fragments (8 pixels of one channel per lane) come from the LDS transpose
+// read ds_read_b64_tr_b16.
 //
 // The image is cut into slices (a range of rows x a range of strips); all
 // channel-block tiles of a slice run on one XCD so that its rows of dy are
@@ -72,16 +74,18 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
     // ---- what this lane fetches -------------------------------------------------
     // dy tile: 512-byte pixel rows, 32 lanes per row; a load covers 2 pixel rows, wave w issues
     // loads w and w + 8 (pixels 2w + prow and 16 + 2w + prow).  Within a row the 32-byte block b
-    // sits at block b ^ (2 * (pixel & 3)): the 4 pixel rows x 2 adjacent blocks a half-wave
-    // transpose read touches then fall on eight different bank ranges.
+    // (16 channels) sits at block b ^ (pixel & 7): the 8 consecutive pixel rows of one block that
+    // a half-wave transpose read touches then fall on eight different bank ranges.
     const int d_prow = lane >> 5, d_pchunk = lane & 31;
     const int d_pix = 2 * wave + d_prow;                 // pixel of the first load; the second is 16 further on
-    const int d_blk = (d_pchunk >> 1) ^ ((d_pix & 3) << 1);
+    const int d_blk = (d_pchunk >> 1) ^ (d_pix & 7);
     const int d_ch = k0 + ((d_blk << 1) | (d_pchunk & 1)) * 8;
     const bool d_ok = d_ch < p.K;
-    // x tile: 64-byte pixel rows (no swizzle needed: four consecutive rows are 256 bytes), 4 lanes
-    // per row, a load covers 16 rows; waves 0..2 issue one each (rows 0..47, 34 used).
-    const int x_row = wave * 16 + (lane >> 2), x_ch = c0 + (lane & 3) * 8;
+    // x tile: [16-channel block][48 rows][16 channels], so that 8 consecutive rows of one block
+    // are 256 contiguous bytes whatever the shift; 16-byte position i = 64 * wave + lane holds
+    // block i / 96, row (i % 96) / 2, half i % 2.  Waves 0..2 issue one load each (rows 0..47, 34 used).
+    const int x_pos = wave * 64 + lane;
+    const int x_row = (x_pos % (2 * XROWS)) >> 1, x_ch = c0 + (x_pos / (2 * XROWS)) * 16 + (x_pos & 1) * 8;
     const bool x_ok = wave < 3 && x_row < PXB + 2 && x_ch < p.C;
 
     // load cursor (wave-uniform): strip ld_xb, step row ld_Y in [Y0 - 2, Y1)
@@ -110,21 +114,23 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
         if (++ld_Y == Y1) { ld_Y = Y0 - 2; ++ld_xb; }
     };
 
-    floatx16_t acc[3][3];
+    floatx4_t acc[3][3][2][2];                           // [r][s][16-k block][16-c block]
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int s = 0; s < 3; ++s)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[r][s][v] = 0.f;
+            for (int ab = 0; ab < 4; ++ab) acc[r][s][ab >> 1][ab & 1] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
     // ---- fragment addressing for the transpose reads ------------------------------
-    // lane = 16*g + q.  As a source it points at pixel 8*(g>>1) + 4*t + q/4 (t = 0, 1: the two
-    // halves of its 8-pixel slice) and channels 16*(g&1) + 4*(q%4)..+3 of a 32-channel MFMA tile;
-    // within a 16-lane group lane i receives element i%4 of the words addressed by lanes 4j + i/4.
+    // lane = 16*g + q.  As a source it points at pixel 16*t + 4*g + q/4 (t = 0, 1: the two halves of
+    // the group's 8 reduction elements; which pixel sits at which reduction position is free as
+    // long as both operands agree) and channels 4*(q%4)..+3 of a 16-channel block; within a
+    // 16-lane group lane i receives element i%4 of the words addressed by lanes 4j + i/4, i.e.
+    // channel i of four pixels.
     const int g = lane >> 4, q = lane & 15;
-    const int f_pix = 8 * (g >> 1) + (q >> 2);
-    const int f_blk = g & 1, f_sub = 4 * (q & 3);
+    const int f_pix = 4 * g + (q >> 2);
+    const int f_sub = 4 * (q & 3);
     auto tr_read = [&](const uint16_t *ptr) {
         return __builtin_amdgcn_ds_read_tr16_b64_v4i16((w3_s16x4_t __attribute__((address_space(3))) *)ptr);
     };
@@ -134,22 +140,19 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
         r[0] = l2[0]; r[1] = l2[1]; r[2] = h2[0]; r[3] = h2[1];
         return r;
     };
-    // dy fragment: this wave's 32 channels, pixels 16*slab .. +15 of the row
-    auto read_dy = [&](const uint16_t *slot, int slab) {
-        const int p0 = 16 * slab + f_pix, p1 = p0 + 4;
-        const int b = 2 * wave + f_blk;
-        const uint16_t *lo = slot + p0 * KB + ((b ^ ((p0 & 3) << 1)) << 4) + f_sub;
-        const uint16_t *hi = slot + p1 * KB + ((b ^ ((p1 & 3) << 1)) << 4) + f_sub;
-        return pack(tr_read(lo), tr_read(hi));
+    // dy fragment: 16-channel block a of this wave's 32 channels, the 32 pixels of the row
+    auto read_dy = [&](const uint16_t *slot, int a) {
+        const int b = 2 * wave + a;
+        const uint16_t *lo = slot + f_pix * KB + ((b ^ (f_pix & 7)) << 4) + f_sub;
+        return pack(tr_read(lo), tr_read(lo + 16 * KB));
     };
-    // x fragment: the 32 channels of the block, pixels 16*slab + s .. +15 of the tile (tile row 0 is pixel x0 - 1)
-    auto read_x = [&](const uint16_t *slot, int slab, int s) {
-        const int p0 = 16 * slab + s + f_pix;
-        const uint16_t *lo = slot + DY_ELEMS + p0 * CB + (f_blk << 4) + f_sub;
-        return pack(tr_read(lo), tr_read(lo + 4 * CB));
+    // x fragment: 16-channel block b, tile rows s .. s + 31 (tile row 0 is pixel x0 - 1)
+    auto read_x = [&](const uint16_t *slot, int b, int s) {
+        const uint16_t *lo = slot + DY_ELEMS + b * (XROWS * 16) + (s + f_pix) * 16 + f_sub;
+        return pack(tr_read(lo), tr_read(lo + 16 * 16));
     };
 
-    u32x4_t fa[3][2], fb[3][2];                          // dy rows (rotating) x slabs; x shifts x slabs
+    u32x4_t fa[3][2], fb[3][2];                          // dy rows (rotating) x k blocks; x shifts x c blocks
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
@@ -185,12 +188,13 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
         issue((k + S - 1) % S);
         sync_phase();
 #pragma unroll
-        for (int slab = 0; slab < 2; ++slab)
+        for (int ab = 0; ab < 4; ++ab)
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                acc[0][s] = T::mfma(fa[n0][slab], fb[s][slab], acc[0][s]);
-                acc[1][s] = T::mfma(fa[n1][slab], fb[s][slab], acc[1][s]);
-                acc[2][s] = T::mfma(fa[n2][slab], fb[s][slab], acc[2][s]);
+                const int a = ab >> 1, b = ab & 1;
+                T::mfma16_acc(acc[0][s][a][b], fa[n0][a], fb[s][b]);
+                T::mfma16_acc(acc[1][s][a][b], fa[n1][a], fb[s][b]);
+                T::mfma16_acc(acc[2][s][a][b], fa[n2][a], fb[s][b]);
             }
     };
 
@@ -212,19 +216,23 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
     }
     if (!late_group) sync_phase();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    mfma_acc_settle();
 
-    // ---- partial sums: register v of lane l holds row k = 8*(v/4) + 4*(l/32) + v%4, column c = l%32 ----
+    // ---- partial sums: register v of lane l of block (a, b) holds k = 16a + 4*(l/16) + v, c = 16b + l%16 ----
     float *out = p.partial + (size_t)slice * p.K * 9 * p.C;
-    const int c = c0 + (lane & 31);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = k0 + wave * 32 + acc_row(v, lane);
-        if (k >= p.K || c >= p.C) continue;
+    for (int ab = 0; ab < 4; ++ab)
 #pragma unroll
-        for (int r = 0; r < 3; ++r)
+        for (int v = 0; v < 4; ++v) {
+            const int a = ab >> 1, b = ab & 1;
+            const int k = k0 + wave * 32 + 16 * a + 4 * (lane >> 4) + v;
+            const int c = c0 + 16 * b + (lane & 15);
+            if (k >= p.K || c >= p.C) continue;
 #pragma unroll
-            for (int s = 0; s < 3; ++s) out[((size_t)k * 9 + r * 3 + s) * p.C + c] = acc[r][s][v];
-    }
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) out[((size_t)k * 9 + r * 3 + s) * p.C + c] = acc[r][s][a][b][v];
+        }
 }
 
 bool wgrad3x3_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw)
