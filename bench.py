@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense fp16/bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 # The dominant kernel: the 3x3 halo-tile implicit-GEMM kernel
-# (igemm_halo3x3_kernel<F16, 2>), which the two full-resolution decoder 3x3
+# (igemm_halo3x3_kernel<F16, 4>), which the two full-resolution decoder 3x3
 # layers (87 % of all FLOPs) run for their forward and data-gradient passes.
 # Timed here on the three calls per step that consist of that kernel alone
 # (plus a microsecond-scale filter re-layout): both forward passes and the
@@ -313,7 +313,7 @@ def main():
                    "loss_hbm_resident": loss_big},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": read_traffic(args.traffic_file),
-                     "kernel": "igemm_halo3x3_kernel<F16, 2>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
+                     "kernel": "igemm_halo3x3_kernel<F16, 4>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
                      "launches_per_step": dom_n,
                      "avg_launch_ms": dom_ms / dom_n, "flop_per_launch": dom_flops / dom_n},
     }

@@ -152,7 +152,8 @@ def test_big_tile_path(api):
 # Shapes that take the halo-tile kernels (stride 1, several taps, >= 200
 # tiles): the 3x3 unit-dilation kernel and the general one; ragged patches,
 # ragged channel chunk, ragged column tile, dilation 2, a column remainder
-# handed to the plain engine, no padding, both data types.
+# handed to the plain engine, no padding, both data types, every column-tile
+# width of the 3x3 kernel (128, 160, <= 64) alone and mixed.
 HALO = [
     (L("halo.ragged", 2, 150, 170, 40, 256, 3, 3, 1, 1, 1), "f16"),
     (L("halo.d2.n192", 1, 230, 250, 32, 192, 3, 3, 1, 2, 2), "bf16"),
@@ -161,6 +162,8 @@ HALO = [
     (L("halo.3x3.n224.c72", 1, 200, 333, 72, 224, 3, 3, 1, 1, 1), "bf16"),
     (L("halo.3x3.nopad", 2, 130, 140, 48, 128, 3, 3, 1, 0, 1), "f16"),
     (L("halo.3x3.k192.narrow-tile", 1, 210, 300, 24, 192, 3, 3, 1, 1, 1), "f16"),
+    (L("halo.3x3.k152.one-160-tile", 1, 200, 280, 24, 152, 3, 3, 1, 1, 1), "bf16"),
+    (L("halo.3x3.k288.128+160", 1, 150, 250, 40, 288, 3, 3, 1, 1, 1), "f16"),
 ]
 
 
