@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
+    ap.add_argument("--deconv-table", action="store_true",
+                    help="instead of the step: time the decoder's transposed-convolution layers (forward, data "
+                         "gradient, filter gradient each) and print a table; no JSON line")
     ap.add_argument("--streams", type=int, default=3, choices=(1, 2, 3, 4),
                     help="2-4: filter gradients of the small layers run on 1-3 more HIP streams beside the "
                          "data-gradient chain")
@@ -151,6 +154,44 @@ def read_traffic(path):
     return None
 
 
+def deconv_table(args):
+    """Transposed-convolution layers of the decoder's up-sampling path (not part of the headline
+    step): HIP-event time of each entry point, median over --steps calls after --warmup."""
+    import torch
+    from paper_1810_01993_amd import api, layers
+
+    torch.cuda.set_device(0)
+    print(f"{'layer (underlying convolution)':34s} {'entry point':28s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s}")
+    for li, layer in enumerate(layers.deconv_layers(2, 768, 1152)):
+        desc = api.desc_from_layer(layer, "f16")
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1000 + li)
+        x = torch.randn((layer.N, layer.P, layer.Q, layer.K), generator=g, device="cuda").abs_().half()
+        sigma = float(np.sqrt(2.0 / (layer.R * layer.S * layer.K)))
+        w = (torch.randn((layer.K, layer.R, layer.S, layer.C), generator=g, device="cuda") * sigma).half()
+        dy = torch.randn((layer.N, layer.H, layer.W, layer.C), generator=g, device="cuda").half()
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        ws = torch.empty(max(16, max(api.dl_conv_workspace_bytes(desc, p) for p in range(3))), dtype=torch.uint8,
+                         device="cuda")
+        calls = {"conv2d_transpose_fwd": lambda: api.conv2d_transpose_fwd(desc, x, w, y=y, workspace=ws),
+                 "conv2d_transpose_bwd_data": lambda: api.conv2d_transpose_bwd_data(desc, dy, w, dx=dx, workspace=ws),
+                 "conv2d_transpose_bwd_filter": lambda: api.conv2d_transpose_bwd_filter(desc, x, dy, dw=dw, workspace=ws)}
+        for name, fn in calls.items():
+            for _ in range(args.warmup):
+                fn()
+            ts = []
+            for _ in range(args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            ms = float(np.median(ts))
+            tf = layer.flops() / (ms * 1e-3) / 1e12
+            print(f"{layer.name:34s} {name:28s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f}", flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -163,6 +204,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.deconv_table:
+        deconv_table(args)
+        return
     _, table = layers.config5()
 
     # one buffer set per occurrence, so repeated shapes do not re-use cache-resident tensors

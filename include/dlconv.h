@@ -95,6 +95,38 @@ dl_status conv2d_bwd_data(const dl_conv_desc *desc, const void *dy, const void *
 dl_status conv2d_bwd_filter(const dl_conv_desc *desc, const void *x, const void *dy, void *dw,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Transposed convolution ("deconvolutional" layer; paper, caption of the
+ * network schematic in Sec. "Segmentation Architecture": the full-resolution
+ * decoder up-samples with such layers).  `desc` names the UNDERLYING
+ * convolution, the one this layer is the adjoint of: the layer maps
+ * x: [N,P,Q,K] to y: [N,H,W,C] with the filter w: [K,R,S,C] (K = the layer's
+ * input channels, C = its output channels),
+ *   y[n,h,w,c] = sum over (p,r),(q,s),k with p*stride_h - pad_h + r*dil_h == h
+ *                and q*stride_w - pad_w + s*dil_w == w of x[n,p,q,k]*w[k,r,s,c],
+ * i.e. every input pixel stamps its filter, scaled, at stride-spaced positions.
+ * The output size (H, W) is part of `desc`, so any size whose forward extent
+ * (dl_conv_out_shape) is (P, Q) can be produced; no separate output padding.
+ * Every element of y is written.  Workspace: dl_conv_workspace_bytes(desc,
+ * DL_PASS_BWD_DATA).  Same dtype, alignment, ownership and error rules as
+ * conv2d_bwd_data, whose arithmetic this is. */
+dl_status conv2d_transpose_fwd(const dl_conv_desc *desc, const void *x, const void *w, void *y,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Gradient of conv2d_transpose_fwd with respect to its input:
+ *   dx[n,p,q,k] = sum_{r,s,c} dy[n, p*stride_h - pad_h + r*dil_h,
+ *                                 q*stride_w - pad_w + s*dil_w, c] * w[k,r,s,c].
+ * dy: [N,H,W,C], dx: [N,P,Q,K].  Workspace: dl_conv_workspace_bytes(desc, DL_PASS_FWD). */
+dl_status conv2d_transpose_bwd_data(const dl_conv_desc *desc, const void *dy, const void *w, void *dx,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Gradient of conv2d_transpose_fwd with respect to its filter:
+ *   dw[k,r,s,c] = sum_{n,p,q} x[n,p,q,k] * dy[n, p*stride_h - pad_h + r*dil_h,
+ *                                              q*stride_w - pad_w + s*dil_w, c].
+ * x: [N,P,Q,K], dy: [N,H,W,C], dw: [K,R,S,C] in `dw_dtype`.  Workspace:
+ * dl_conv_workspace_bytes(desc, DL_PASS_BWD_FILTER). */
+dl_status conv2d_transpose_bwd_filter(const dl_conv_desc *desc, const void *x, const void *dy, void *dw,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Scratch bytes for weighted_pixel_ce_fwd_bwd on n_pixels pixels. */
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes);
 

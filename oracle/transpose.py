@@ -29,7 +29,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import ConvShape, conv_bwd_filter, conv_fwd, out_shape
+from . import ConvShape, conv_bwd_filter, conv_bwd_filter_at, conv_fwd, conv_fwd_at, out_shape
 
 
 def _geometry(s: ConvShape):
@@ -117,3 +117,13 @@ def conv_transpose_bwd_filter(s: ConvShape, x, dy) -> np.ndarray:
     the filter-gradient sum of the underlying convolution with the roles of
     its input (here dy) and its output gradient (here x) as named there."""
     return conv_bwd_filter(s, dy, x)
+
+
+def conv_transpose_bwd_data_at(s: ConvShape, dy32, w32, flat_idx) -> np.ndarray:
+    """dx.ravel()[flat_idx] (float32 storage, double arithmetic); same sum as above."""
+    return conv_fwd_at(s, dy32, w32, flat_idx)
+
+
+def conv_transpose_bwd_filter_at(s: ConvShape, x32, dy32, flat_idx) -> np.ndarray:
+    """dw.ravel()[flat_idx] (float32 storage, double arithmetic); same sum as above."""
+    return conv_bwd_filter_at(s, dy32, x32, flat_idx)

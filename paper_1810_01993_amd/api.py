@@ -20,7 +20,8 @@ DL_F16, DL_BF16, DL_F32 = 0, 1, 2
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data",
-           "conv2d_bwd_filter", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "dl_status_string")
+           "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
+           "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "dl_status_string")
 
 
 class DlError(RuntimeError):
@@ -69,7 +70,8 @@ def _load() -> ctypes.CDLL:
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     lib.dl_conv_out_shape.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
     lib.dl_conv_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(sz)]
-    for name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_filter"):
+    for name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_filter", "conv2d_transpose_fwd",
+                 "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter"):
         getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
     lib.weighted_pixel_ce_fwd_bwd.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64,
@@ -185,6 +187,59 @@ def conv2d_bwd_filter(desc: ConvDesc, x: torch.Tensor, dy: torch.Tensor, dw: tor
     ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_BWD_FILTER), x.device, workspace)
     _check(_lib.conv2d_bwd_filter(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(dy), _dev_ptr(dw),
                                   _dev_ptr(ws), nb, _stream()), "conv2d_bwd_filter")
+    return dw
+
+
+def conv2d_transpose_fwd(desc: ConvDesc, x: torch.Tensor, w: torch.Tensor, y: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """x: [N,P,Q,K] -> y: [N,H,W,C]; ``desc`` names the underlying convolution (see the header)."""
+    P, Q = dl_conv_out_shape(desc)
+    _expect(x, (desc.N, P, Q, desc.K), "x")
+    _expect(w, (desc.K, desc.R, desc.S, desc.C), "w")
+    if _dtype_code(x) != desc.dtype or w.dtype != x.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    if y is None:
+        y = torch.empty((desc.N, desc.H, desc.W, desc.C), dtype=x.dtype, device=x.device)
+    _expect(y, (desc.N, desc.H, desc.W, desc.C), "y")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_BWD_DATA), x.device, workspace)
+    _check(_lib.conv2d_transpose_fwd(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(w), _dev_ptr(y),
+                                     _dev_ptr(ws), nb, _stream()), "conv2d_transpose_fwd")
+    return y
+
+
+def conv2d_transpose_bwd_data(desc: ConvDesc, dy: torch.Tensor, w: torch.Tensor, dx: torch.Tensor | None = None,
+                              workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """dy: [N,H,W,C] -> dx: [N,P,Q,K]."""
+    P, Q = dl_conv_out_shape(desc)
+    _expect(dy, (desc.N, desc.H, desc.W, desc.C), "dy")
+    _expect(w, (desc.K, desc.R, desc.S, desc.C), "w")
+    if _dtype_code(dy) != desc.dtype or w.dtype != dy.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    if dx is None:
+        dx = torch.empty((desc.N, P, Q, desc.K), dtype=dy.dtype, device=dy.device)
+    _expect(dx, (desc.N, P, Q, desc.K), "dx")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_FWD), dy.device, workspace)
+    _check(_lib.conv2d_transpose_bwd_data(ctypes.byref(desc.c_struct()), _dev_ptr(dy), _dev_ptr(w), _dev_ptr(dx),
+                                          _dev_ptr(ws), nb, _stream()), "conv2d_transpose_bwd_data")
+    return dx
+
+
+def conv2d_transpose_bwd_filter(desc: ConvDesc, x: torch.Tensor, dy: torch.Tensor, dw: torch.Tensor | None = None,
+                                workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """x: [N,P,Q,K], dy: [N,H,W,C] -> dw: [K,R,S,C]."""
+    P, Q = dl_conv_out_shape(desc)
+    _expect(x, (desc.N, P, Q, desc.K), "x")
+    _expect(dy, (desc.N, desc.H, desc.W, desc.C), "dy")
+    if _dtype_code(x) != desc.dtype or dy.dtype != x.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    dwt = desc.dtype if desc.dw_dtype is None else desc.dw_dtype
+    if dw is None:
+        dw = torch.empty((desc.K, desc.R, desc.S, desc.C), device=x.device,
+                         dtype=torch.float32 if dwt == DL_F32 else x.dtype)
+    _expect(dw, (desc.K, desc.R, desc.S, desc.C), "dw")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_BWD_FILTER), x.device, workspace)
+    _check(_lib.conv2d_transpose_bwd_filter(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(dy), _dev_ptr(dw),
+                                            _dev_ptr(ws), nb, _stream()), "conv2d_transpose_bwd_filter")
     return dw
 
 

@@ -349,6 +349,27 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     return hip_status(e);
 }
 
+// The transposed convolution and its two gradients are the three passes of the underlying
+// convolution with the operand roles exchanged: the layer's input stands where that
+// convolution's output gradient stands, its output where the data gradient stands.
+dl_status conv2d_transpose_fwd(const dl_conv_desc *d, const void *x, const void *w, void *y, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    return conv2d_bwd_data(d, x, w, y, workspace, workspace_bytes, hip_stream);
+}
+
+dl_status conv2d_transpose_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, void *dx, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream)
+{
+    return conv2d_fwd(d, dy, w, dx, workspace, workspace_bytes, hip_stream);
+}
+
+dl_status conv2d_transpose_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy, void *dw,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return conv2d_bwd_filter(d, dy, x, dw, workspace, workspace_bytes, hip_stream);
+}
+
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes)
 {
     if (!bytes) return DL_ERR_NULL;

@@ -132,6 +132,19 @@ def config4():
     ]
 
 
+def deconv_layers(N: int = 2, H: int = 768, W: int = 1152):
+    """The decoder's up-sampling path as transposed convolutions (the network
+    schematic's caption names deconvolutional layers in the full-resolution
+    decoder; it does not give their shapes).  Reading: 3x3, stride 2, padding 1,
+    256 -> 256 channels, each doubling the resolution, from the encoder's
+    output stride 16 up to full resolution.  Each entry is the UNDERLYING
+    convolution (the layer is its adjoint): (H, W, C) is the layer's output,
+    K its input channels, (P, Q) = (H/2, W/2) its input size."""
+    L = ConvLayer
+    return [L(f"deconv.3x3.s2.256.to-{H // f}x{W // f}", N, H // f, W // f, 256, 256, 3, 3, 2, 1, 1, 1)
+            for f in (8, 4, 2, 1)]
+
+
 def config5():
     """Whole conv stack + loss, one GPU's share, fp16."""
     return "f16", deeplab_layers(2, 768, 1152, True)
