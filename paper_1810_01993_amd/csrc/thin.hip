@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void thin_wgrad_kernel(const WgradArgs p)
         if (pl < lanes) {
 #pragma unroll 4
             for (int pix = sub + pl; pix < sub_end; pix += lanes) {
-                const u32x4_t xv = *reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8);
+                const u32x4_t xv = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8));
                 float xf[8];
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
