@@ -270,7 +270,13 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
     // Input pixels (h, w) fall into stride_h*stride_w parity classes; within a
     // class the contributing taps and the output pixels they pair with form
     // regular grids, so each class is one dense implicit GEMM over dy with the
-    // filter re-laid-out as [c][tap][k].
+    // filter re-laid-out as [c][tap][k].  Classes that take the plain engine with
+    // one tile shape share a launch (their tiles of one image region then run
+    // side by side); the others are launched one by one.
+    struct Pending { dlk::IgemmArgs a; FilterSrc fs; uint16_t *blk; };
+    Pending pending[dlk::IgemmBatch::MAX];
+    int n_pending = 0;
+    bool overflow = false;
     size_t ws_off = 0;
     for (int ca = 0; ca < d->stride_h; ++ca)
         for (int cb = 0; cb < d->stride_w; ++cb) {
@@ -306,8 +312,26 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
             }
             const FilterSrc fs{static_cast<const uint16_t *>(w), c.th.r0 * SC + (int64_t)c.tw.r0 * d->C, 1,
                                c.th.rstep * SC, (int64_t)c.tw.rstep * d->C, (int64_t)d->R * SC};
+            if (c.has_taps && halo_columns(a) == 0 && !overflow) {
+                if (n_pending < dlk::IgemmBatch::MAX) {
+                    pending[n_pending++] = Pending{a, fs, blk};
+                    continue;
+                }
+                overflow = true;                        // more classes than one launch holds: one by one after all
+            }
             if (run_igemm(a, bf16, fs, blk, stream) != hipSuccess) return DL_ERR_LAUNCH;
         }
+    if (n_pending > 0) {
+        dlk::IgemmBatch b{};
+        b.n = n_pending;
+        for (int i = 0; i < n_pending; ++i) b.a[i] = pending[i].a;
+        if (!overflow && dlk::igemm_batch_cfg(b.a, b.n) >= 0) {
+            if (dlk::launch_igemm_batch(b, bf16, stream) != hipSuccess) return DL_ERR_LAUNCH;
+        } else {
+            for (int i = 0; i < n_pending; ++i)
+                if (run_igemm(pending[i].a, bf16, pending[i].fs, pending[i].blk, stream) != hipSuccess) return DL_ERR_LAUNCH;
+        }
+    }
     return DL_OK;
 }
 

@@ -40,8 +40,10 @@ typedef short bt_s16x4_t __attribute__((ext_vector_type(4)));
 // Its tile is deposited as it lies in memory, [32 reduction channels][BN columns], 32-byte blocks of a
 // row XOR-swizzled with the row index, and the MFMA fragments (8 consecutive reduction channels of one
 // column per lane) come from ds_read_b64_tr_b16, as in the filter-gradient kernels.
-template <class T, int BM, int BN, int WM, int WN, bool CMAJOR, bool BT = false>
-__global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs p)
+// The body of the kernel: workgroup `tile` of the GEMM p (tiles are numbered column tile fastest),
+// range `split` of a split reduction.
+template <class T, int BM, int BN, int WM, int WN, bool CMAJOR, bool BT>
+__device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int tile, const int split)
 {
     static_assert(!BT || CMAJOR, "a reduction-major filter needs the channel-major order");
     constexpr int NW = WM * WN;
@@ -64,7 +66,6 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     const int NT = p.TR * p.TS;                       // taps
     const int Kred = NT * p.Cin;
     const int tiles_n = (p.Nout + BN - 1) / BN;
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
     const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
@@ -124,7 +125,6 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     // ---- reduction cursor ---------------------------------------------------
     // channel-major: (t, jr, js, c0) are wave-uniform; tap-major: (kk, c, js, jr) per lane
     // channels [c_first, c_end) of the reduction belong to this workgroup (all of them unless the reduction is split)
-    const int split = blockIdx.y;
     int c_first = 0, c_end = p.Cin;
     if (CMAJOR && p.ksplits > 1) {
         c_first = split * p.split_chunks * BK;
@@ -352,6 +352,27 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs 
     }
 }
 
+template <class T, int BM, int BN, int WM, int WN, bool CMAJOR, bool BT = false>
+__global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs p)
+{
+    igemm_dma_tile<T, BM, BN, WM, WN, CMAJOR, BT>(p, xcd_remap(blockIdx.x, gridDim.x), blockIdx.y);
+}
+
+// Several small GEMMs of one tile shape in one launch (the stride-parity classes of a strided
+// data gradient on a small image, each of which alone is a ~10 us kernel): workgroup ids are
+// dealt to the GEMMs in turn.  Channel-major order only.
+template <class T, int BM, int BN, int WM, int WN, bool BT>
+__global__ __launch_bounds__(WM *WN * 64) void igemm_dma_batch_kernel(const IgemmBatch b)
+{
+    const int id = xcd_remap(blockIdx.x, gridDim.x);
+    const int which = id % b.n, tile = id / b.n;
+    const IgemmArgs &p = b.a[which];
+    const int64_t M = (int64_t)p.NB * p.OH * p.OW;
+    const int64_t tiles = ((M + BM - 1) / BM) * ((p.Nout + BN - 1) / BN);
+    if (tile >= tiles) return;                           // this GEMM has fewer tiles than the largest
+    igemm_dma_tile<T, BM, BN, WM, WN, true, BT>(p, tile, 0);
+}
+
 template <class T, int BM, int BN, int WM, int WN>
 static hipError_t launch_dma_cfg(const IgemmArgs &a, hipStream_t stream)
 {
@@ -380,6 +401,44 @@ static hipError_t dispatch_dma(const IgemmArgs &a, int cfg, hipStream_t stream)
         case 8: return launch_dma_cfg<T, 64, 64, 2, 1>(a, stream);     // 2 waves, wave tile 32x64
         default: return hipErrorInvalidValue;
     }
+}
+
+template <class T, int BM, int BN, int WM, int WN>
+static hipError_t launch_dma_batch_cfg(const IgemmBatch &b, hipStream_t stream)
+{
+    int64_t tiles_max = 0;
+    for (int i = 0; i < b.n; ++i) {
+        const IgemmArgs &a = b.a[i];
+        if (!a.c_outer || a.ksplits > 1 || a.b_transposed != b.a[0].b_transposed) return hipErrorInvalidValue;
+        if (a.b_transposed && a.Nout % 8 != 0) return hipErrorInvalidValue;
+        const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+        const int64_t tiles = ((M + BM - 1) / BM) * ((a.Nout + BN - 1) / BN);
+        if (tiles > tiles_max) tiles_max = tiles;
+    }
+    if (tiles_max <= 0 || tiles_max * b.n > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(tiles_max * b.n)), block(WM * WN * 64);
+    if (b.a[0].b_transposed) hipLaunchKernelGGL((igemm_dma_batch_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((igemm_dma_batch_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, b);
+    return hipGetLastError();
+}
+
+template <class T>
+static hipError_t dispatch_dma_batch(const IgemmBatch &b, int cfg, hipStream_t stream)
+{
+    switch (cfg) {
+        case 0: return launch_dma_batch_cfg<T, 256, 256, 2, 4>(b, stream);
+        case 2: return launch_dma_batch_cfg<T, 128, 128, 2, 2>(b, stream);
+        case 3: return launch_dma_batch_cfg<T, 128, 64, 2, 2>(b, stream);
+        case 4: return launch_dma_batch_cfg<T, 64, 32, 2, 1>(b, stream);
+        case 8: return launch_dma_batch_cfg<T, 64, 64, 2, 1>(b, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_igemm_dma_batch(const IgemmBatch &b, bool is_bf16, int cfg, hipStream_t stream)
+{
+    if (b.n < 1 || b.n > IgemmBatch::MAX) return hipErrorInvalidValue;
+    return is_bf16 ? dispatch_dma_batch<BF16>(b, cfg, stream) : dispatch_dma_batch<F16>(b, cfg, stream);
 }
 
 hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream_t stream)

@@ -43,6 +43,20 @@ struct IgemmArgs {
     int32_t b_elems;            // elements of the tensor B points into (bounds of the loads)
 };
 
+// Up to four GEMMs for one launch of the direct-to-LDS engine (see igemm_dma_batch_kernel).
+struct IgemmBatch {
+    static constexpr int MAX = 4;
+    IgemmArgs a[MAX];
+    int32_t n;
+};
+
+// Tile configuration (as for launch_igemm_dma) if these n GEMMs can share one launch of the
+// direct-to-LDS engine, or -1: all must take the same configuration of the plain engine in
+// channel-major order, unsplit, with the filter given the same way.
+int igemm_batch_cfg(const IgemmArgs *a, int n);
+hipError_t launch_igemm_batch(const IgemmBatch &b, bool is_bf16, hipStream_t stream);
+hipError_t launch_igemm_dma_batch(const IgemmBatch &b, bool is_bf16, int cfg, hipStream_t stream);
+
 // Would launch_igemm accept this GEMM with a reduction-major filter (b_transposed)?
 bool igemm_accepts_transposed_b(const IgemmArgs &a);
 
