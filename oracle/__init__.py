@@ -89,6 +89,9 @@ def _load():
         lib.oracle_weighted_ce.argtypes = [dp, ctypes.POINTER(ctypes.c_uint8), dp, ctypes.c_double,
                                            ctypes.c_int64, ctypes.c_int32, dp, dp]
         lib.oracle_weighted_ce.restype = None
+        lib.oracle_weighted_ce_map.argtypes = [dp, ctypes.POINTER(ctypes.c_uint8), dp, ctypes.c_double,
+                                               ctypes.c_int64, ctypes.c_int32, dp, dp]
+        lib.oracle_weighted_ce_map.restype = None
         _lib = lib
     return _lib
 
@@ -191,4 +194,26 @@ def weighted_ce(z, labels, class_weights, scale, want_grad=True):
     _load().oracle_weighted_ce(_dp(z), labels.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _dp(cw),
                                ctypes.c_double(scale), ctypes.c_int64(n), ctypes.c_int32(n_classes),
                                ctypes.byref(loss), _dp(dz) if want_grad else None)
+    return loss.value, dz
+
+
+def weighted_ce_map(z, labels, weight_map, scale, want_grad=True):
+    """The loss with a per-pixel weight map (one weight per pixel, any values).
+    Returns (loss, dz).  z: [..., n_classes]; labels, weight_map: [...]."""
+    z = _d(z)
+    n_classes = z.shape[-1]
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    n = labels.size
+    if z.size != n * n_classes:
+        raise ValueError("z and labels disagree on the pixel count")
+    if n and int(labels.max()) >= n_classes:
+        raise ValueError("label out of range")
+    wm = _d(weight_map)
+    if wm.size != n:
+        raise ValueError("weight map and labels disagree on the pixel count")
+    loss = ctypes.c_double(0.0)
+    dz = np.empty_like(z) if want_grad else None
+    _load().oracle_weighted_ce_map(_dp(z), labels.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _dp(wm),
+                                   ctypes.c_double(scale), ctypes.c_int64(n), ctypes.c_int32(n_classes),
+                                   ctypes.byref(loss), _dp(dz) if want_grad else None)
     return loss.value, dz

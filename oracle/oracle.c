@@ -257,3 +257,31 @@ void oracle_weighted_ce(const double *z, const uint8_t *labels, const double *cw
     }
     *loss = scale * total;
 }
+
+/* ---- the same loss with the weight given per pixel ------------------------ */
+/* Sec. "Weighted loss": the per-pixel weight map is computed by the input
+ * pipeline and handed to the GPU with the image.  l_i and the softmax are as
+ * above; the weight of pixel i is wmap[i] instead of cw[label_i]. */
+void oracle_weighted_ce_map(const double *z, const uint8_t *labels, const double *wmap, double scale,
+                            int64_t n_pixels, int32_t n_classes, double *loss, double *dz)
+{
+    double total = 0.0;
+    for (int64_t i = 0; i < n_pixels; ++i) {
+        const double *zi = z + (size_t)i * n_classes;
+        int lab = labels[i];
+        double m = zi[0];
+        for (int c = 1; c < n_classes; ++c)
+            if (zi[c] > m) m = zi[c];
+        double se = 0.0;
+        for (int c = 0; c < n_classes; ++c) se += exp(zi[c] - m);
+        double lse = m + log(se);
+        total += wmap[i] * (lse - zi[lab]);
+        if (dz) {
+            for (int c = 0; c < n_classes; ++c) {
+                double pc = exp(zi[c] - lse);
+                dz[(size_t)i * n_classes + c] = scale * wmap[i] * (pc - (c == lab ? 1.0 : 0.0));
+            }
+        }
+    }
+    *loss = scale * total;
+}

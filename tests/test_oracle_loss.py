@@ -130,3 +130,58 @@ def test_class_weights_follow_the_paper():
     ratio = synth.CLASS_WEIGHTS[2] / synth.CLASS_WEIGHTS[0]
     assert 25 < ratio < 40
     assert not (25 < (f_bg / synth.CLASS_FREQ[2]) < 40)      # inverse frequency is ruled out
+
+
+# ---- the same loss with a per-pixel weight map (the form the paper feeds the GPU) ----
+def test_map_hand_example(oracle):
+    # the two pixels of the hand example above with weights that no class table could give
+    # (both pixels could carry the same label and still weigh differently)
+    z = np.array([[0.0, math.log(2), math.log(3)], [math.log(4), 0.0, 0.0]])
+    lab = np.array([2, 1], dtype=np.uint8)
+    loss, dz = oracle.weighted_ce_map(z, lab, np.array([3.0, 0.25]), 2.0)
+    assert abs(loss - 2.0 * (3.0 * math.log(2) + 0.25 * math.log(6))) < 1e-12
+    expect = 2.0 * np.array([[3 / 6, 6 / 6, 9 / 6 - 3], [1 / 6, 0.25 / 6 - 0.25, 0.25 / 6]])
+    np.testing.assert_allclose(dz, expect, rtol=0, atol=1e-12)
+
+
+def test_map_gathered_from_the_class_table_is_the_class_weighted_loss(oracle):
+    z, lab = _case(11)
+    cw = np.array(synth.CLASS_WEIGHTS)
+    la, da = oracle.weighted_ce(z, lab, cw, 1.0 / len(lab))
+    lb, db = oracle.weighted_ce_map(z, lab, cw[lab], 1.0 / len(lab))
+    assert abs(la - lb) < 1e-13
+    np.testing.assert_allclose(da, db, rtol=0, atol=1e-15)
+
+
+def test_map_matches_library_per_pixel_losses(oracle):
+    import torch
+    import torch.nn.functional as F
+    z, lab = _case(12)
+    wm = np.random.default_rng(13).uniform(0.0, 40.0, len(lab))
+    wm[::7] = 0.0                                   # masked-out pixels contribute nothing
+    loss, dz = oracle.weighted_ce_map(z, lab, wm, 0.01)
+    zt = torch.tensor(z, requires_grad=True)
+    per_pixel = F.cross_entropy(zt, torch.tensor(lab.astype(np.int64)), reduction="none")
+    lt = 0.01 * (per_pixel * torch.tensor(wm)).sum()
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-11
+    np.testing.assert_allclose(dz, zt.grad.numpy(), rtol=0, atol=1e-13)
+    assert np.all(dz[::7] == 0.0)
+
+
+def test_map_is_linear_in_the_weights_and_finite_differences(oracle):
+    z, lab = _case(14, n=33)
+    g = np.random.default_rng(15)
+    wa, wb = g.uniform(0, 5, 33), g.uniform(0, 5, 33)
+    la, da = oracle.weighted_ce_map(z, lab, wa, 0.3)
+    lb, db = oracle.weighted_ce_map(z, lab, wb, 0.3)
+    lc, dc = oracle.weighted_ce_map(z, lab, 2 * wa + wb, 0.3)
+    assert abs(lc - (2 * la + lb)) < 1e-12
+    np.testing.assert_allclose(dc, 2 * da + db, rtol=0, atol=1e-13)
+    eps = 1e-5
+    for _ in range(10):
+        i, c = g.integers(0, 33), g.integers(0, 3)
+        e = np.zeros_like(z); e[i, c] = eps
+        lp, _ = oracle.weighted_ce_map(z + e, lab, wa, 0.3, want_grad=False)
+        lm, _ = oracle.weighted_ce_map(z - e, lab, wa, 0.3, want_grad=False)
+        assert abs((lp - lm) / (2 * eps) - da[i, c]) < 1e-7 * max(1.0, abs(da[i, c]))
