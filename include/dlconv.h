@@ -145,6 +145,17 @@ dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uin
                                     float *loss, void *dlogits,
                                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same loss with the weight given per pixel (paper, Sec. "Weighted loss":
+ * the per-pixel weight map is computed by the input pipeline and handed to the
+ * GPU with the image): weight_map[i] stands where class_weights[label_i]
+ * stands above.  weight_map: device float[n_pixels], 16-byte aligned, any
+ * values (0 masks a pixel out).  17 bytes of traffic per pixel instead of 13.
+ * Everything else as for weighted_pixel_ce_fwd_bwd. */
+dl_status weighted_pixel_ce_map_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,
+                                        const float *weight_map, float scale, int64_t n_pixels,
+                                        float *loss, void *dlogits,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
 const char *dl_status_string(dl_status s);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
-           "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "dl_status_string")
+           "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
 
 
 class DlError(RuntimeError):
@@ -74,8 +74,8 @@ def _load() -> ctypes.CDLL:
                  "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter"):
         getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
-    lib.weighted_pixel_ce_fwd_bwd.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64,
-                                              vp, vp, vp, sz, vp]
+    for name in ("weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd"):
+        getattr(lib, name).argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     lib.dl_status_string.argtypes = [ctypes.c_int]
@@ -264,6 +264,30 @@ def weighted_pixel_ce_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, class_
                                           _dev_ptr(class_weights), ctypes.c_float(scale), n, _dev_ptr(loss),
                                           _dev_ptr(dlogits), _dev_ptr(ws), nb, _stream()),
            "weighted_pixel_ce_fwd_bwd")
+    return loss, dlogits
+
+
+def weighted_pixel_ce_map_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, weight_map: torch.Tensor,
+                                  scale: float, loss: torch.Tensor | None = None,
+                                  dlogits: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """The loss with a per-pixel weight map: weight_map float32 [...] (device), one
+    weight per pixel.  Returns (loss: float32[1] device tensor, dlogits)."""
+    if logits.shape[-1] != 3:
+        raise ValueError("3 classes expected in the last dimension")
+    n = labels.numel()
+    if logits.numel() != 3 * n or labels.dtype != torch.uint8:
+        raise ValueError("labels must be uint8 with one entry per pixel")
+    if weight_map.dtype != torch.float32 or weight_map.numel() != n:
+        raise ValueError("weight_map must be float32 with one entry per pixel")
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=logits.device)
+    if dlogits is None:
+        dlogits = torch.empty_like(logits)
+    ws, nb = _workspace(dl_ce_workspace_bytes(n), logits.device, workspace)
+    _check(_lib.weighted_pixel_ce_map_fwd_bwd(_dev_ptr(logits), _dtype_code(logits), _dev_ptr(labels),
+                                              _dev_ptr(weight_map), ctypes.c_float(scale), n, _dev_ptr(loss),
+                                              _dev_ptr(dlogits), _dev_ptr(ws), nb, _stream()),
+           "weighted_pixel_ce_map_fwd_bwd")
     return loss, dlogits
 
 

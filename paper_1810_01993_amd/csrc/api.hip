@@ -402,22 +402,40 @@ dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes)
     return DL_OK;
 }
 
+namespace {
+dl_status run_ce(const void *logits, int32_t dtype, const uint8_t *labels, const float *weights, bool per_pixel,
+                 float scale, int64_t n_pixels, float *loss, void *dlogits, void *workspace, size_t workspace_bytes,
+                 void *hip_stream)
+{
+    if (!loss || (!weights && (!per_pixel || n_pixels > 0))) return DL_ERR_NULL;
+    if (n_pixels < 0 || n_pixels >= MAX_ELEMS * 16) return DL_ERR_SHAPE;
+    if (n_pixels > 0 && (!logits || !labels || !dlogits)) return DL_ERR_NULL;
+    if (dtype != DL_F16 && dtype != DL_BF16) return DL_ERR_DTYPE;
+    if (!aligned16(logits) || !aligned16(labels) || !aligned16(dlogits) || (per_pixel && !aligned16(weights)))
+        return DL_ERR_ALIGN;
+    const size_t need = (size_t)dlk::ce_num_blocks(n_pixels) * sizeof(float);
+    if (!workspace || workspace_bytes < need) return DL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DL_ERR_ALIGN;
+    return hip_status(dlk::launch_weighted_ce(static_cast<const uint16_t *>(logits), dtype == DL_BF16, labels, weights,
+                                              per_pixel, scale, n_pixels, loss, static_cast<uint16_t *>(dlogits),
+                                              static_cast<float *>(workspace), static_cast<hipStream_t>(hip_stream)));
+}
+}  // namespace
+
 dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,
                                     const float *class_weights, float scale, int64_t n_pixels, float *loss,
                                     void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!class_weights || !loss) return DL_ERR_NULL;
-    if (n_pixels < 0 || n_pixels >= MAX_ELEMS * 16) return DL_ERR_SHAPE;
-    if (n_pixels > 0 && (!logits || !labels || !dlogits)) return DL_ERR_NULL;
-    if (dtype != DL_F16 && dtype != DL_BF16) return DL_ERR_DTYPE;
-    if (!aligned16(logits) || !aligned16(labels) || !aligned16(dlogits)) return DL_ERR_ALIGN;
-    const size_t need = (size_t)dlk::ce_num_blocks(n_pixels) * sizeof(float);
-    if (!workspace || workspace_bytes < need) return DL_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return DL_ERR_ALIGN;
-    return hip_status(dlk::launch_weighted_ce(static_cast<const uint16_t *>(logits), dtype == DL_BF16, labels,
-                                              class_weights, scale, n_pixels, loss,
-                                              static_cast<uint16_t *>(dlogits), static_cast<float *>(workspace),
-                                              static_cast<hipStream_t>(hip_stream)));
+    return run_ce(logits, dtype, labels, class_weights, false, scale, n_pixels, loss, dlogits, workspace,
+                  workspace_bytes, hip_stream);
+}
+
+dl_status weighted_pixel_ce_map_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,
+                                        const float *weight_map, float scale, int64_t n_pixels, float *loss,
+                                        void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_ce(logits, dtype, labels, weight_map, true, scale, n_pixels, loss, dlogits, workspace, workspace_bytes,
+                  hip_stream);
 }
 
 }  // extern "C"

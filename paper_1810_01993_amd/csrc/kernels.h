@@ -150,9 +150,9 @@ hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n,
 
 // Weighted per-pixel cross-entropy, 3 classes.
 int ce_num_blocks(int64_t n_pixels);
-hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *cw,
-                              float scale, int64_t n_pixels, float *loss, uint16_t *dlogits, float *partials,
-                              hipStream_t stream);
+hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
+                              bool per_pixel, float scale, int64_t n_pixels, float *loss, uint16_t *dlogits,
+                              float *partials, hipStream_t stream);
 
 
 }  // namespace dlk

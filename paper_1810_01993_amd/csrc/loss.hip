@@ -37,14 +37,12 @@ int ce_num_blocks(int64_t n_pixels)
 }
 
 // One pixel: returns w * (logsumexp - z_label) and overwrites z0..z2 with the gradient.
-__device__ __forceinline__ float ce_pixel(float &z0, float &z1, float &z2, int lab, float w0, float w1, float w2,
-                                          float scale)
+__device__ __forceinline__ float ce_pixel(float &z0, float &z1, float &z2, int lab, float w, float scale)
 {
     const float m = fmaxf(z0, fmaxf(z1, z2));
     const float e0 = __expf(z0 - m), e1 = __expf(z1 - m), e2 = __expf(z2 - m);
     const float se = e0 + e1 + e2;
     const float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
-    const float w = lab == 0 ? w0 : (lab == 1 ? w1 : w2);
     const float l = w * (m + __logf(se) - zl);
     const float g = scale * w / se;
     z0 = g * e0 - (lab == 0 ? scale * w : 0.f);
@@ -53,13 +51,16 @@ __device__ __forceinline__ float ce_pixel(float &z0, float &z1, float &z2, int l
     return l;
 }
 
-template <class T>
+// MAP: `cw` is a per-pixel weight map (float[n]) instead of the 3-entry class table.
+template <class T, bool MAP>
 __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restrict__ logits,
                                                         const uint8_t *__restrict__ labels,
                                                         const float *__restrict__ cw, float scale, int64_t n,
                                                         uint16_t *__restrict__ dlogits, float *__restrict__ partials)
 {
-    const float w0 = cw[0], w1 = cw[1], w2 = cw[2];
+    float w0 = 0.f, w1 = 0.f, w2 = 0.f;
+    if (!MAP) { w0 = cw[0]; w1 = cw[1]; w2 = cw[2]; }
+    auto weight = [&](int lab, float from_map) { return MAP ? from_map : (lab == 0 ? w0 : (lab == 1 ? w1 : w2)); };
     float sum = 0.f;
     const int64_t full_groups = n / 8;
     const int64_t stride = (int64_t)gridDim.x * CE_THREADS;
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
     // the loads of the next trip are issued before the current one is worked on
     u32x4_t n0{}, n1{}, n2{};
     u32x2_t nlb{};
+    floatx4_t nw0{}, nw1{};                              // MAP: the weights of the lane's 8 pixels
     auto fetch = [&](int64_t t) {
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(logits + t * (64 * 24));
         // streamed: nothing is touched twice (with these hints 5.7 instead of 5.0 TB/s on an HBM-resident tensor)
@@ -82,12 +84,18 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
         n1 = __builtin_nontemporal_load(src + 64 + lane);
         n2 = __builtin_nontemporal_load(src + 128 + lane);
         nlb = *reinterpret_cast<const u32x2_t *>(labels + (t * 64 + lane) * 8);
+        if (MAP) {
+            const floatx4_t *wsrc = reinterpret_cast<const floatx4_t *>(cw + (t * 64 + lane) * 8);
+            nw0 = __builtin_nontemporal_load(wsrc);
+            nw1 = __builtin_nontemporal_load(wsrc + 1);
+        }
     };
     const int64_t t_first = (int64_t)blockIdx.x * (CE_THREADS / 64) + wave;
     if (t_first < wave_trips) fetch(t_first);
     for (int64_t t = t_first; t < wave_trips; t += wstride) {
         const u32x4_t c0 = n0, c1 = n1, c2 = n2;
         const u32x2_t lb = nlb;
+        const floatx4_t wa = nw0, wb = nw1;
         if (t + wstride < wave_trips) fetch(t + wstride);
         my[lane] = c0; my[64 + lane] = c1; my[128 + lane] = c2;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
 #pragma unroll
         for (int px = 0; px < 8; ++px) {
             const int lab = (lb[px >> 2] >> (8 * (px & 3))) & 0xff;
-            sum += ce_pixel(z[3 * px], z[3 * px + 1], z[3 * px + 2], lab, w0, w1, w2, scale);
+            sum += ce_pixel(z[3 * px], z[3 * px + 1], z[3 * px + 2], lab, weight(lab, px < 4 ? wa[px & 3] : wb[px & 3]), scale);
         }
 #pragma unroll
         for (int i = 0; i < 12; ++i)
@@ -127,6 +135,11 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(logits + g * 24);
         u32x4_t v[3] = {src[0], src[1], src[2]};
         const u32x2_t lb = *reinterpret_cast<const u32x2_t *>(labels + g * 8);
+        float wm[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (MAP) {
+#pragma unroll
+            for (int px = 0; px < 8; ++px) wm[px] = cw[g * 8 + px];
+        }
         float z[24];
 #pragma unroll
         for (int i = 0; i < 12; ++i) {
@@ -137,7 +150,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
 #pragma unroll
         for (int px = 0; px < 8; ++px) {
             const int lab = (lb[px >> 2] >> (8 * (px & 3))) & 0xff;
-            sum += ce_pixel(z[3 * px], z[3 * px + 1], z[3 * px + 2], lab, w0, w1, w2, scale);
+            sum += ce_pixel(z[3 * px], z[3 * px + 1], z[3 * px + 2], lab, weight(lab, wm[px]), scale);
         }
 #pragma unroll
         for (int i = 0; i < 12; ++i)
@@ -152,7 +165,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(const uint16_t *__restri
         const int64_t i = full_groups * 8 + threadIdx.x;
         if (threadIdx.x < 8 && i < n) {
             float z0 = T::to_float(logits[i * 3]), z1 = T::to_float(logits[i * 3 + 1]), z2 = T::to_float(logits[i * 3 + 2]);
-            sum += ce_pixel(z0, z1, z2, labels[i], w0, w1, w2, scale);
+            sum += ce_pixel(z0, z1, z2, labels[i], weight(labels[i], MAP ? cw[i] : 0.f), scale);
             dlogits[i * 3] = T::from_float(z0);
             dlogits[i * 3 + 1] = T::from_float(z1);
             dlogits[i * 3 + 2] = T::from_float(z2);
@@ -180,17 +193,20 @@ __global__ __launch_bounds__(CE_THREADS) void ce_finish_kernel(const float *__re
     if (threadIdx.x == 0) loss[0] = scale * ((wsum[0] + wsum[1]) + (wsum[2] + wsum[3]));
 }
 
-hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *cw,
-                              float scale, int64_t n_pixels, float *loss, uint16_t *dlogits, float *partials,
-                              hipStream_t stream)
+hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
+                              bool per_pixel, float scale, int64_t n_pixels, float *loss, uint16_t *dlogits,
+                              float *partials, hipStream_t stream)
 {
     const int blocks = ce_num_blocks(n_pixels);
-    if (is_bf16)
-        hipLaunchKernelGGL(ce_kernel<BF16>, dim3(blocks), dim3(CE_THREADS), 0, stream, logits, labels, cw, scale,
-                           n_pixels, dlogits, partials);
+    const dim3 grid(blocks), block(CE_THREADS);
+    if (is_bf16 && per_pixel)
+        hipLaunchKernelGGL((ce_kernel<BF16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+    else if (is_bf16)
+        hipLaunchKernelGGL((ce_kernel<BF16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+    else if (per_pixel)
+        hipLaunchKernelGGL((ce_kernel<F16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
     else
-        hipLaunchKernelGGL(ce_kernel<F16>, dim3(blocks), dim3(CE_THREADS), 0, stream, logits, labels, cw, scale,
-                           n_pixels, dlogits, partials);
+        hipLaunchKernelGGL((ce_kernel<F16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, blocks, scale, loss);

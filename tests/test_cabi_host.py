@@ -76,4 +76,10 @@ def test_pointer_checks_happen_before_any_launch(api):
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, -1, 16, 16, 16, 64, None) == 2
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 16, None, 0, None) == 5
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 24, 16, 64, None) == 4
+    assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, None, 1.0, 8, 16, 16, 16, 64, None) == 1   # no weight map
+    assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, 24, 1.0, 8, 16, 16, 16, 64, None) == 4     # map misaligned
+    assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 16, None, 0, None) == 5
+    for fn in (lib.conv2d_transpose_fwd, lib.conv2d_transpose_bwd_data, lib.conv2d_transpose_bwd_filter):
+        assert fn(ref, None, None, None, None, 0, None) == 1
+        assert fn(ref, 16, 16, 24, None, 0, None) == 4
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)

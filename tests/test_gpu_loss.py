@@ -84,3 +84,55 @@ def test_determinism_and_redzones(api):
         assert torch.all(buf[:guard] == 77.0) and torch.all(buf[-guard:] == 77.0)
         res.append((loss.clone(), dz.clone()))
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+def test_more_pixels_than_one_trip_per_wavefront(api):
+    # above 1024 workgroups x 4 wavefronts x 512 pixels a wavefront makes several trips (the
+    # loads of the next trip are in flight while the current one is worked on)
+    # (scale 2^-10 rather than 1/n: with 4 M pixels 1/n would put every gradient in fp16's
+    # subnormal range, where the spacing of 6e-8 is 4e-3 of the largest gradient)
+    n = 2 * 1024 * 4 * 512 + 8 * 70 + 3
+    _run(api, n, "f16", synth.seed_for(0, 960), scale=2.0 ** -10)
+
+
+# ---- per-pixel weight map --------------------------------------------------------
+def _run_map(api, n, dtype, seed, from_table=False):
+    print(f"[case] weighted_ce_map n={n} {dtype} seed={seed} from_table={from_table}", flush=True)
+    sys.stdout.flush()
+    z32, zb = synth.quantize(synth.normal(seed, (n, 3)), dtype)
+    labels = synth.rng(seed + 1).choice(3, size=n, p=synth.CLASS_FREQ).astype(np.uint8)
+    if from_table:
+        wm = np.asarray(synth.CLASS_WEIGHTS, dtype=np.float32)[labels]
+    else:
+        wm = synth.rng(seed + 2).uniform(0.0, 40.0, n).astype(np.float32)
+        wm[::5] = 0.0                                   # masked-out pixels
+    scale = 1.0 / max(n, 1)
+    zd, ld, wd = U.to_device(zb, dtype), torch.from_numpy(labels).cuda(), torch.from_numpy(wm).cuda()
+    loss, dz = api.weighted_pixel_ce_map_fwd_bwd(zd, ld, wd, scale)
+    torch.cuda.synchronize()
+    ref_loss, ref_dz = oracle.weighted_ce_map(z32, labels, wm.astype(np.float64), float(np.float32(scale)))
+    got_loss = float(loss.item())
+    if n == 0:
+        assert got_loss == 0.0
+        return
+    assert abs(got_loss - ref_loss) <= LOSS_RTOL * abs(ref_loss), (got_loss, ref_loss)
+    g = U.to_host_f64(dz)
+    assert U.rel_err(g, ref_dz) <= U.TOL[dtype]
+    if not from_table:
+        assert np.all(g[::5] == 0.0)
+    else:
+        # the class-table entry point must give the very same bits
+        cw = torch.tensor(synth.CLASS_WEIGHTS, dtype=torch.float32, device="cuda")
+        loss2, dz2 = api.weighted_pixel_ce_fwd_bwd(zd, ld, cw, scale)
+        assert torch.equal(dz, dz2) and torch.equal(loss, loss2)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("n", [0, 1, 7, 9, 1000, 8 * 257 + 3, 8 * 256 * 9 + 5])
+def test_weight_map_sizes_and_ragged_tails(api, n, dtype):
+    _run_map(api, n, dtype, synth.seed_for(0, 970 + n % 89))
+
+
+def test_weight_map_full_mask_and_class_table_equivalence(api):
+    _run_map(api, 2 * 768 * 1152, "f16", synth.seed_for(5, 995), from_table=True)
+    _run_map(api, 2 * 1024 * 4 * 512 + 8 * 70 + 3, "bf16", synth.seed_for(0, 996))
