@@ -1,0 +1,41 @@
+"""fp64 CPU oracle for the forward convolution with the point-wise tail fused
+into it: y = act(conv(x, w) + bias).
+
+TEST INFRASTRUCTURE ONLY, like the rest of this package.
+
+The paper counts bias layers among the point-wise operations around the
+convolutions and names fusing point-wise operations, so that tensors are read
+and written fewer times, as the optimisation being pursued (Sec. "Single GPU
+Performance").  The definition is the convolution of ``oracle.c`` followed by
+  y[n,p,q,k] <- y[n,p,q,k] + bias[k]            (bias: one value per output channel)
+  y          <- max(y, 0)                        (if relu)
+applied to the un-rounded fp64 sums.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import ConvShape, conv_fwd, conv_fwd_at
+
+
+def conv_fwd_bias_relu(s: ConvShape, x, w, bias=None, relu: bool = False) -> np.ndarray:
+    y = conv_fwd(s, x, w)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        if b.shape != (s.K,):
+            raise ValueError("bias must have one entry per output channel")
+        y = y + b[None, None, None, :]
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
+
+
+def conv_fwd_bias_relu_at(s: ConvShape, x32, w32, bias, relu: bool, flat_idx) -> np.ndarray:
+    """Single output elements (float32 storage, double arithmetic)."""
+    idx = np.asarray(flat_idx, dtype=np.int64)
+    y = conv_fwd_at(s, x32, w32, idx)
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[idx % s.K]
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
