@@ -76,6 +76,17 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
 dl_status conv2d_fwd(const dl_conv_desc *desc, const void *x, const void *w, void *y,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* conv2d_fwd with the point-wise tail fused into the store (paper, Sec.
+ * "Single GPU Performance": bias layers are among the point-wise operations
+ * around the convolutions, and fusing point-wise operations so that tensors
+ * are read and written fewer times is the optimisation being pursued):
+ *   y[n,p,q,k] = act(conv2d_fwd(x, w)[n,p,q,k] + bias[k]),
+ * act = max(., 0) if relu != 0, identity otherwise.  bias: device float[K]
+ * (4-byte aligned) or NULL for none; it is added to the fp32 sum, which is then
+ * cut and rounded once.  Everything else as for conv2d_fwd (same workspace). */
+dl_status conv2d_fwd_bias_relu(const dl_conv_desc *desc, const void *x, const void *w, const float *bias,
+                               int32_t relu, void *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Data gradient (paper, Sec. "Deep learning ...": each layer is
  * differentiable; backward convolutions in the kernel breakdown): the adjoint
  * of conv2d_fwd with respect to x applied to dy.

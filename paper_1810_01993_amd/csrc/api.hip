@@ -110,6 +110,7 @@ hipError_t run_igemm(const dlk::IgemmArgs &a, bool bf16, const FilterSrc &fs, ui
     r.Nout = a.Nout - cols;
     r.B = a.B + (size_t)cols * a.TR * a.TS * a.Cin;
     r.D = a.D + cols;
+    if (a.bias) r.bias = a.bias + cols;
     return dlk::launch_igemm(r, bf16, stream);
 }
 
@@ -233,14 +234,16 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
     return DL_ERR_UNSUPPORTED;
 }
 
-dl_status conv2d_fwd(const dl_conv_desc *d, const void *x, const void *w, void *y, void *workspace,
-                     size_t workspace_bytes, void *hip_stream)
+namespace {
+dl_status run_fwd(const dl_conv_desc *d, const void *x, const void *w, const float *bias, int relu, void *y,
+                  void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!d || !x || !w || !y) return DL_ERR_NULL;
     Geometry g;
     const dl_status st = check_desc(d, &g);
     if (st != DL_OK) return st;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return DL_ERR_ALIGN;
+    if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return DL_ERR_ALIGN;
     dlk::IgemmArgs a = fwd_args(d, g);
     const size_t need = igemm_scratch_bytes(a);
     if (need > 0 && (!workspace || workspace_bytes < need)) return DL_ERR_WORKSPACE;
@@ -248,9 +251,24 @@ dl_status conv2d_fwd(const dl_conv_desc *d, const void *x, const void *w, void *
     a.A = static_cast<const uint16_t *>(x);
     a.B = static_cast<const uint16_t *>(w);
     a.D = static_cast<uint16_t *>(y);
+    a.bias = bias;
+    a.relu = relu ? 1 : 0;
     const FilterSrc fs{a.B, 0, (int64_t)d->R * d->S * d->C, (int64_t)d->S * d->C, d->C, 1};
     return hip_status(run_igemm(a, d->dtype == DL_BF16, fs, static_cast<uint16_t *>(workspace),
                                 static_cast<hipStream_t>(hip_stream)));
+}
+}  // namespace
+
+dl_status conv2d_fwd(const dl_conv_desc *d, const void *x, const void *w, void *y, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    return run_fwd(d, x, w, nullptr, 0, y, workspace, workspace_bytes, hip_stream);
+}
+
+dl_status conv2d_fwd_bias_relu(const dl_conv_desc *d, const void *x, const void *w, const float *bias, int32_t relu,
+                               void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_fwd(d, x, w, bias, relu, y, workspace, workspace_bytes, hip_stream);
 }
 
 dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, void *dx, void *workspace,

@@ -74,6 +74,33 @@ __device__ __forceinline__ void mfma_acc_settle()
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 }
 
+// Point-wise tail of the forward convolution (bias per output column, then ReLU), applied to
+// the fp32 sums before they are rounded.  bias and relu are kernel arguments (uniform).
+__device__ __forceinline__ float apply_tail(float v, const float *bias, int relu, int col)
+{
+    if (bias) v += bias[col];
+    return relu ? fmaxf(v, 0.f) : v;
+}
+// four consecutive columns col .. col+3 of which those below ncols exist
+__device__ __forceinline__ floatx4_t apply_tail4(floatx4_t c, const float *bias, int relu, int col, int ncols)
+{
+    if (bias) {
+        if (col + 3 < ncols && ((reinterpret_cast<uintptr_t>(bias + col) & 15) == 0)) {
+            const floatx4_t b = *reinterpret_cast<const floatx4_t *>(bias + col);
+            c += b;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < ncols) c[e] += bias[col + e];
+        }
+    }
+    if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = fmaxf(c[e], 0.f);
+    }
+    return c;
+}
+
 // LDS tiles are [rows][BKT] 16-bit elements (BKT = 32 or 64) with the row
 // pitch padded by 8 elements (16 bytes): pitch/16 is then odd, so the 16-byte
 // fragment reads of 8 consecutive rows fall into 8 different 16-byte bank groups.

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
                 row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
             }
             const int col = n0 + wn * 32 + (lane & 31);
-            if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][0][v]);
+            if (col < p.Nout) p.D[row_off + col] = T::from_float(apply_tail(acc[i][0][v], p.bias, p.relu, col));
         }
 }
 
@@ -230,7 +230,8 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
                 b.split_chunks = cps;
                 hipError_t e = launch_igemm_dma(b, std::is_same<T, BF16>::value, 0, stream);      // 256 x 256 tiles
                 if (e != hipSuccess) return e;
-                return launch_splitk_reduce(a.part, ks, M * a.Nout, a.D, std::is_same<T, BF16>::value ? 1 : 0, stream);
+                return launch_splitk_reduce_tail(a.part, ks, M * a.Nout, a.D, std::is_same<T, BF16>::value ? 1 : 0, a.bias,
+                                                 a.relu, a.Nout, stream);
             }
         }
         // A ragged last column tile of the widest configuration (e.g. 304 = 256 + 48 output
@@ -243,6 +244,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
             if (a.b_transposed) hi.b_base = a.b_base + lo.Nout;
             else hi.B = a.B + (size_t)lo.Nout * a.TR * a.TS * a.Cin;
             hi.D = a.D + lo.Nout;
+            if (a.bias) hi.bias = a.bias + lo.Nout;
             hipError_t e = launch_igemm_dma(lo, std::is_same<T, BF16>::value, 0, stream);
             if (e != hipSuccess) return e;
             return launch_igemm_dma(hi, std::is_same<T, BF16>::value, rem <= 64 ? 3 : 2, stream);

@@ -308,17 +308,19 @@ __device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int til
     uint16_t *stg = lds + wave * 32 * EP;
     const bool dense = (p.osh == 1 && p.osw == 1 && p.FH == p.OH && p.FW == p.OW);
     const bool vec_ok = (p.ldd % 8 == 0) && (p.Nout % 8 == 0) && ((reinterpret_cast<uintptr_t>(p.D) & 15) == 0);
+    const bool tail = p.bias != nullptr || p.relu != 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const floatx16_t &c = acc[i][j];
-                u32x2_t pk;
-                pk[0] = (uint32_t)T::from_float(c[4 * g]) | ((uint32_t)T::from_float(c[4 * g + 1]) << 16);
-                pk[1] = (uint32_t)T::from_float(c[4 * g + 2]) | ((uint32_t)T::from_float(c[4 * g + 3]) << 16);
                 const int row = lane & 31, ch = j * 32 + 8 * g + 4 * (lane >> 5);
+                floatx4_t c{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (tail) c = apply_tail4(c, p.bias, p.relu, n0 + wn * CH + ch, p.Nout);
+                u32x2_t pk;
+                pk[0] = (uint32_t)T::from_float(c[0]) | ((uint32_t)T::from_float(c[1]) << 16);
+                pk[1] = (uint32_t)T::from_float(c[2]) | ((uint32_t)T::from_float(c[3]) << 16);
                 *reinterpret_cast<u32x2_t *>(stg + row * EP + ch) = pk;
             }
 #pragma unroll

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(512) void igemm_halo_kernel(const IgemmArgs p)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                if (col < p.Nout) p.D[row_off + col] = T::from_float(acc[i][j][v]);
+                if (col < p.Nout) p.D[row_off + col] = T::from_float(apply_tail(acc[i][j][v], p.bias, p.relu, col));
             }
         }
     }

@@ -251,6 +251,7 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
     static_assert(NW * 64 * EP <= 2 * H_ELEMS + S * B_ELEMS, "staging area must fit the tile buffers");
     uint16_t *stg = lds + wave * 64 * EP;
     const bool vec_ok = (p.ldd % 8 == 0) && (p.Nout % 8 == 0) && ((reinterpret_cast<uintptr_t>(p.D) & 15) == 0);
+    const bool tail = p.bias != nullptr || p.relu != 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -259,7 +260,8 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
             for (int n = 0; n < NB; ++n)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) {
-                    const floatx4_t &c = acc[2 * h + ii][n][b];
+                    floatx4_t c = acc[2 * h + ii][n][b];
+                    if (tail) c = apply_tail4(c, p.bias, p.relu, n0 + wn * CH + n * 16 + 4 * (lane >> 4), p.Nout);
                     u32x2_t pk;
                     pk[0] = (uint32_t)T::from_float(c[0]) | ((uint32_t)T::from_float(c[1]) << 16);
                     pk[1] = (uint32_t)T::from_float(c[2]) | ((uint32_t)T::from_float(c[3]) << 16);
@@ -333,6 +335,7 @@ hipError_t launch_columns(const IgemmArgs &a, bool is_bf16, hipStream_t stream, 
     IgemmArgs w = a;
     w.Nout = ncols;
     w.D = a.D + col_first;
+    if (a.bias) w.bias = a.bias + col_first;
     if (is_bf16) hipLaunchKernelGGL((igemm_halo3x3_kernel<BF16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
     else hipLaunchKernelGGL((igemm_halo3x3_kernel<F16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
     return hipGetLastError();

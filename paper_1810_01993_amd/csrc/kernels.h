@@ -41,6 +41,10 @@ struct IgemmArgs {
     int32_t b_transposed;
     int32_t b_base, b_sr, b_ss, b_ldk;
     int32_t b_elems;            // elements of the tensor B points into (bounds of the loads)
+    // Point-wise tail fused into the store: D = act(sum + bias[column]).  bias: fp32, one value per
+    // output column of THIS launch (null: none); relu != 0: negative results become zero.
+    const float *bias;
+    int32_t relu;
 };
 
 // Up to four GEMMs for one launch of the direct-to-LDS engine (see igemm_dma_batch_kernel).
@@ -147,6 +151,9 @@ hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t strea
 // dw[i] = sum_z partial[z][i] in ascending z, rounded to out_dtype (dl_dtype).
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                 hipStream_t stream);
+// The same with the forward convolution's point-wise tail: element i belongs to column i % ncols.
+hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
+                                     const float *bias, int32_t relu, int32_t ncols, hipStream_t stream);
 
 // Weighted per-pixel cross-entropy, 3 classes.
 int ce_num_blocks(int64_t n_pixels);

@@ -43,6 +43,8 @@ __global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
                 s0 += a[c] * b[e][c];
                 s1 += a[c] * b[e + 1][c];
             }
+            s0 = apply_tail(s0, p.bias, p.relu, j + e);
+            s1 = apply_tail(s1, p.bias, p.relu, j + e + 1);
             out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
         }
         // streamed store: the output (0.9 GB for the logits layer) is far larger than the caches

@@ -236,7 +236,7 @@ hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 // only on `splits`, never on timing.
 template <int OUT>   // 0 f16, 1 bf16, 2 f32
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n,
-                                                            void *out)
+                                                            void *out, const float *__restrict__ bias, int relu, int ncols)
 {
     __shared__ float part[4][64];
     const int x = threadIdx.x & 63, g = threadIdx.x >> 6;
@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
         part[g][x] = (s0 + s1) + (s2 + s3);
         __syncthreads();
         if (g == 0 && i < n) {
-            const float s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            float s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            if (bias || relu) s = apply_tail(s, bias, relu, (int)(i % ncols));
             if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
             else if constexpr (OUT == 1) reinterpret_cast<uint16_t *>(out)[i] = BF16::from_float(s);
             else reinterpret_cast<float *>(out)[i] = s;
@@ -265,16 +266,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
+hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
+                                     const float *bias, int32_t relu, int32_t ncols, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    if (ncols < 1) return hipErrorInvalidValue;
+    const int64_t want = (n + 63) / 64;
+    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
+    if (out_dtype == 0)
+        hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+    else if (out_dtype == 1)
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+    return hipGetLastError();
+}
+
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                 hipStream_t stream)
 {
-    if (n <= 0) return hipSuccess;
-    const int64_t want = (n + 63) / 64;
-    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
-    if (out_dtype == 0) hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out);
-    else if (out_dtype == 1) hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out);
-    else hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out);
-    return hipGetLastError();
+    return launch_splitk_reduce_tail(partial, splits, n, out, out_dtype, nullptr, 0, 1, stream);
 }
 
 }  // namespace dlk

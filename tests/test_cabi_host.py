@@ -82,4 +82,6 @@ def test_pointer_checks_happen_before_any_launch(api):
     for fn in (lib.conv2d_transpose_fwd, lib.conv2d_transpose_bwd_data, lib.conv2d_transpose_bwd_filter):
         assert fn(ref, None, None, None, None, 0, None) == 1
         assert fn(ref, 16, 16, 24, None, 0, None) == 4
+    assert lib.conv2d_fwd_bias_relu(ref, None, 16, None, 1, 16, None, 0, None) == 1
+    assert lib.conv2d_fwd_bias_relu(ref, 16, 16, 18, 1, 16, None, 0, None) == 4                    # bias not 4-byte aligned
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)
