@@ -156,8 +156,15 @@ DgradClass dgrad_class(const dl_conv_desc *d, const Geometry &g, int ca, int cb)
     return c;
 }
 
+bool use_dgrad_stem(const dl_conv_desc *d)
+{
+    return dlk::dgrad_stem_applicable(d->N, d->H, d->W, d->C, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+                                      d->dil_h, d->dil_w);
+}
+
 size_t dgrad_workspace(const dl_conv_desc *d, const Geometry &g)
 {
+    if (use_dgrad_stem(d)) return align_up(dlk::dgrad_stem_filter_bytes(d->C, d->K), 256);
     size_t total = 0;
     for (int ca = 0; ca < d->stride_h; ++ca)
         for (int cb = 0; cb < d->stride_w; ++cb) {
@@ -284,6 +291,22 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
     if (need > 0 && !aligned16(workspace)) return DL_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf16 = d->dtype == DL_BF16;
+
+    if (use_dgrad_stem(d)) {
+        // few input channels, 7x7 stride 2: all parity classes in one workgroup, operands resident in LDS
+        dlk::FilterBlockArgs f{};
+        f.src = static_cast<const uint16_t *>(w);
+        f.dst = static_cast<uint16_t *>(workspace);
+        f.base = 0; f.sj = 1; f.sr = (int64_t)d->S * d->C; f.ss = d->C; f.sc = (int64_t)d->R * d->S * d->C;
+        f.Nrows = d->C; f.TR = d->R; f.TS = d->S; f.Cin = d->K;
+        if (dlk::launch_filter_block(f, stream) != hipSuccess) return DL_ERR_LAUNCH;
+        dlk::DgradStemArgs a{};
+        a.dy = static_cast<const uint16_t *>(dy);
+        a.wblk = f.dst;
+        a.dx = static_cast<uint16_t *>(dx);
+        a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.P = g.P; a.Q = g.Q;
+        return hip_status(dlk::launch_dgrad_stem(a, bf16, stream));
+    }
 
     // Input pixels (h, w) fall into stride_h*stride_w parity classes; within a
     // class the contributing taps and the output pixels they pair with form

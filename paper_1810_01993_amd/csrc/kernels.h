@@ -92,6 +92,19 @@ struct FilterBlockArgs {
 };
 hipError_t launch_filter_block(const FilterBlockArgs &a, hipStream_t stream);
 
+// Data gradient of a 7x7, stride-2, padding-3 convolution with 8 or 16 input channels and at most
+// 64 output channels (the stem): all four parity classes in one workgroup, operands resident in LDS.
+// wblk: the filter as [chunk of K][tap][c][32] (launch_filter_block with rows = c).
+struct DgradStemArgs {
+    const uint16_t *dy;         // [N][P][Q][K]
+    const uint16_t *wblk;
+    uint16_t *dx;               // [N][H][W][C]
+    int32_t N, H, W, C, K, P, Q;
+};
+bool dgrad_stem_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw);
+size_t dgrad_stem_filter_bytes(int C, int K);
+hipError_t launch_dgrad_stem(const DgradStemArgs &a, bool is_bf16, hipStream_t stream);
+
 // Filter re-layout for the data gradient: for one stride-parity class,
 //   wt[c][jr][js][k] = w[k][r0 + jr*rstep][s0 + js*sstep][c]
 struct FilterRelayoutArgs {

@@ -172,6 +172,22 @@ def test_halo_tile_kernel(api, layer, dtype):
     check_layer(api, layer, dtype, synth.seed_for(0, 600 + len(layer.name)), x_kind="normal", n_samples=8192)
 
 
+# 7x7 / stride 2 / padding 3 with 8 or 16 input channels: the data gradient takes the kernel that
+# keeps the filter and a dy patch resident in LDS; odd and even image sizes (ragged patches, the
+# last output row belonging to one parity class only), one and two chunks of K, ragged K chunk.
+STEM = [
+    (L("stem.c16.k64", 2, 61, 75, 16, 64, 7, 7, 2, 3, 1), "f16"),
+    (L("stem.c16.k40.even", 1, 64, 96, 16, 40, 7, 7, 2, 3, 1), "bf16"),
+    (L("stem.c8.k24", 1, 33, 130, 8, 24, 7, 7, 2, 3, 1), "f16"),
+    (L("stem.c16.k8.tiny", 3, 5, 7, 16, 8, 7, 7, 2, 3, 1), "bf16"),
+]
+
+
+@pytest.mark.parametrize("layer,dtype", STEM, ids=[l.name for l, _ in STEM])
+def test_stem_data_gradient_kernel(api, layer, dtype):
+    check_layer(api, layer, dtype, synth.seed_for(0, 650 + len(layer.name)), x_kind="normal", passes=("dgrad",))
+
+
 def test_wgrad_3x3_fused_taps(api):
     # large-image 3x3 filter gradient (all taps per workgroup): ragged strip, ragged channel block, ragged k
     check_layer(api, L("wgrad3x3.ragged", 1, 330, 1000, 40, 72, 3, 3, 1, 1, 1), "bf16", synth.seed_for(0, 700),
