@@ -397,6 +397,7 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w; a.dh = d->dil_h; a.dw = d->dil_w;
     a.splits = plan.splits;
     a.chunk = plan.chunk;
+    a.spread = plan.spread;
     hipError_t e;
     if (plan.cfg == -3) {
         const dlk::Wgrad3x3Plan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);

@@ -125,6 +125,7 @@ struct WgradArgs {
     int32_t sh, sw, ph, pw, dh, dw;
     int32_t splits;             // slices of the pixel range
     int32_t chunk;              // pixels per slice, multiple of 32
+    int32_t spread;             // direct-to-LDS kernel: deal the tiles of a slice over all XCDs (few slices)
 };
 hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream);
 
@@ -137,6 +138,7 @@ struct WgradPlan {
     int cfg;
     int splits;
     int chunk;                  // pixels per slice, multiple of 32
+    int spread;                 // see WgradArgs
 };
 WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok);
 

@@ -74,8 +74,11 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_dma_kernel(const WgradArgs 
     // Workgroups are dealt to the 8 XCDs round-robin by id.  All tiles of one
     // pixel slice are given to the same XCD, back to back, so that the slice of
     // dy and x they all read is fetched into that XCD's L2 once.
+    // With few slices (small images with large filters) that would leave XCDs idle: then
+    // consecutive ids take consecutive tiles of a slice, i.e. every slice runs on all XCDs.
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const int tile = slot % tiles, split = (slot / tiles) * 8 + xcd;
+    const int tile = p.spread ? (int)(blockIdx.x % tiles) : slot % tiles;
+    const int split = p.spread ? (int)(blockIdx.x / tiles) : (slot / tiles) * 8 + xcd;
     if (split >= p.splits) return;                         // uniform for the whole workgroup
     const int k0 = (tile / tiles_n) * BM, j0 = (tile % tiles_n) * BN;
     const int pix_begin = split * p.chunk;
@@ -222,7 +225,7 @@ static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
     const int RSC = a.R * a.S * a.C;
     const int64_t tiles = (int64_t)((a.K + BM - 1) / BM) * ((RSC + BN - 1) / BN);
     const int64_t split_groups = (a.splits + 7) / 8;        // each XCD takes every 8th slice
-    const int64_t blocks = tiles * split_groups * 8;
+    const int64_t blocks = a.spread ? tiles * a.splits : tiles * split_groups * 8;
     if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((wgrad_dma_kernel<T, BM, BN, WM, WN, STAGES>), dim3((unsigned)blocks), dim3(WM * WN * 64), 0,
                        stream, a);
@@ -235,7 +238,7 @@ WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
         const char *e = std::getenv("DLCONV_WGRAD_CFG");      // tuning override, unset in normal use
         return e ? std::atoi(e) : -2;
     }();
-    WgradPlan pl{-1, 1, 32};
+    WgradPlan pl{-1, 1, 32, 0};
     if (thin_ok && forced != -1) {
         // streaming kernel: one workgroup per slice of pixels, about eight slices per CU
         int64_t s = (npix + 255) / 256;
@@ -280,17 +283,19 @@ WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
         const Shape &sh = shapes[cfg];
         const int64_t tiles = (int64_t)((K + sh.bm - 1) / sh.bm) * ((RSC + sh.bn - 1) / sh.bn);
         const int64_t cap = 32 * sh.per_cu;                  // workgroups one XCD holds at a time
-        for (int cand = 0; cand < 67; ++cand) {
-            // 1, 2, 4 slices (fewer than XCDs), then 8, 16, ... 512: the same number on every XCD
-            int64_t s = cand < 3 ? (1 << cand) : 8 * (cand - 2);
+        for (int cand = 0; cand < 64 + 15; ++cand) {
+            // 8, 16, ... 512 slices, the same number on every XCD, each slice on one XCD; or
+            // 1 .. 15 slices whose tiles are dealt over all XCDs
+            const bool spread = cand >= 64;
+            int64_t s = spread ? cand - 63 : 8 * (cand + 1);
             if (forced_target > 0) s = (forced_target + tiles - 1) / tiles;
-            if (s > 512) break;
-            if (s > 1 && s * 128 > npix) break;              // at least four 32-pixel steps per slice
+            if (s > 512) continue;
+            if (s > 1 && s * 128 > npix) continue;           // at least four 32-pixel steps per slice
             int64_t chunk = (npix + s - 1) / s;
             chunk = (chunk + 31) / 32 * 32;
             const int64_t splits = (npix + chunk - 1) / chunk;
             const int64_t per_xcd = (splits + 7) / 8;
-            const int64_t rounds = (tiles * per_xcd + cap - 1) / cap;
+            const int64_t rounds = spread ? (tiles * splits + 8 * cap - 1) / (8 * cap) : (tiles * per_xcd + cap - 1) / cap;
             const double reduce_us = (splits > 1 ? splits * outputs * 8.0 : outputs * 6.0) / 11.5e6;
             const double est = 9.0 + rounds * (chunk / 32 + 7) * sh.us_per_step + reduce_us;
             if (est < best) {
@@ -298,8 +303,9 @@ WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
                 pl.cfg = cfg;
                 pl.chunk = (int)chunk;
                 pl.splits = (int)splits;
+                pl.spread = spread ? 1 : 0;
             }
-            if (forced_target > 0) break;
+            if (forced_target > 0 && spread) break;
         }
     }
     return pl;
