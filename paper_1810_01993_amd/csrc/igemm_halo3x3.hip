@@ -161,16 +161,19 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
     const int hbase = (wm * TM) * HW + frow;             // halo pixel of (first patch row of the wave, column frow), shift 0
 
     u32x4_t fa[TM + 2][2], fb[NB];
-    // the six halo rows under the wave's four patch rows, at column shift cs; [][b]: pixels 16*b .. +15 of the row
-    auto read_rows = [&]() {
-        const uint16_t *hal = sH + (chunk & 1) * H_ELEMS;
+    // Halo row r (0..5) under the wave's four patch rows, at column shift cs_ of chunk ch_'s image;
+    // [][b]: pixels 16*b .. +15 of the row.  The six rows of a column shift are not read in one
+    // step: rows 2, 3 in the step of row shift 0, row 4 with row shift 1 and row 5 with row shift 2
+    // (when they are first needed), and rows 0, 1 one step ahead, in the last step of the previous
+    // column shift, whose products no longer use those registers.  That spreads the LDS reads
+    // evenly over the steps (with the filter: 8, 6 and 10 instead of 16, 4 and 4).
+    auto read_row = [&](int r, int cs_, int ch_) __attribute__((always_inline)) {
+        const uint16_t *hal = sH + (ch_ & 1) * H_ELEMS;
 #pragma unroll
-        for (int r = 0; r < TM + 2; ++r)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int h = hbase + r * HW + cs + 16 * b;
-                fa[r][b] = *reinterpret_cast<const u32x4_t *>(hal + h * BK + ((fsl ^ p3_swz(h)) << 3));
-            }
+        for (int b = 0; b < 2; ++b) {
+            const int h = hbase + r * HW + cs_ + 16 * b;
+            fa[r][b] = *reinterpret_cast<const u32x4_t *>(hal + h * BK + ((fsl ^ p3_swz(h)) << 3));
+        }
     };
     auto read_filter = [&](int slot) {
         const uint16_t *wb = sB + slot * B_ELEMS + wn * CH * BK + foff;
@@ -198,7 +201,21 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
         constexpr int k = decltype(kc)::value;
         constexpr int u = k % 3;
         sync_loaded();
-        if (u == 0) read_rows();
+        if (u == 0) {
+            if (chunk == 0 && cs == 0) { read_row(0, 0, 0); read_row(1, 0, 0); }   // nobody read them ahead
+            read_row(2, cs, chunk);
+            read_row(3, cs, chunk);
+        } else if (u == 1) {
+            read_row(4, cs, chunk);
+        } else {
+            read_row(5, cs, chunk);
+            // The next column shift's rows 0, 1.  Across a chunk boundary they come from the next
+            // chunk's image: its pieces that hold these rows (halo pixels < 512: pieces 0..3 of every
+            // wave) were issued in steps 0..3 of this chunk, i.e. five or more steps ago: landed.
+            const int ncs = cs == 2 ? 0 : cs + 1, nch = cs == 2 ? chunk + 1 : chunk;
+            read_row(0, ncs, nch);
+            read_row(1, ncs, nch);
+        }
         read_filter(k);
         issue_filter((k + S - 1) % S);                   // the slot the previous step has finished with
         const int q = cs * 3 + u;                        // step within the chunk
