@@ -39,3 +39,23 @@ def conv_fwd_bias_relu_at(s: ConvShape, x32, w32, bias, relu: bool, flat_idx) ->
     if relu:
         y = np.maximum(y, 0.0)
     return y
+
+
+def bias_relu_bwd(dy, y, relu: bool = True):
+    """Backward of the point-wise tail y = act(s + bias[k]) given dy = dL/dy and the forward
+    output y ([..., K] each):
+      dz[i,k]  = dy[i,k] if (not relu or y[i,k] > 0) else 0      (= dL/ds, what the convolution's
+                                                                   gradient kernels take)
+      dbias[k] = sum_i dz[i,k]
+    (the derivative of max(., 0) at 0 is taken as 0, as y = 0 carries no sign)."""
+    dy = np.asarray(dy, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    if dy.shape != y.shape:
+        raise ValueError("shape mismatch")
+    dz = np.where(y > 0.0, dy, 0.0) if relu else dy.copy()
+    K = dy.shape[-1]
+    dbias = np.zeros(K, dtype=np.float64)
+    flat = dz.reshape(-1, K)
+    for i in range(flat.shape[0]):          # pixel by pixel, in index order
+        dbias += flat[i]
+    return dz, dbias

@@ -48,3 +48,30 @@ def test_properties_and_single_elements(oracle):
     x32, w32 = x.astype(np.float32), w.astype(np.float32)
     ref = E.conv_fwd_bias_relu(s, x32.astype(np.float64), w32.astype(np.float64), b, True).ravel()[idx]
     assert np.allclose(E.conv_fwd_bias_relu_at(s, x32, w32, b, True, idx), ref, rtol=0, atol=1e-13)
+
+
+def test_tail_backward_hand_example():
+    y = np.array([[1.0, 0.0, 2.0], [0.0, 3.0, 0.5]])
+    dy = np.array([[10.0, 20.0, 30.0], [1.0, 2.0, 3.0]])
+    dz, db = E.bias_relu_bwd(dy, y, True)
+    assert np.array_equal(dz, [[10.0, 0.0, 30.0], [0.0, 2.0, 3.0]])
+    assert np.array_equal(db, [10.0, 2.0, 33.0])
+    dz, db = E.bias_relu_bwd(dy, y, False)
+    assert np.array_equal(dz, dy) and np.array_equal(db, [11.0, 22.0, 33.0])
+
+
+def test_tail_backward_against_autograd(oracle):
+    s = ConvShape(2, 7, 9, 5, 6, 3, 3, 1, 1, 1)
+    x, w, b = _rand(20, 2, 7, 9, 5), _rand(21, 6, 3, 3, 5), _rand(22, 6)
+    dy = _rand(23, 2, 7, 9, 6)
+    y = E.conv_fwd_bias_relu(s, x, w, b, True)
+    dz, db = E.bias_relu_bwd(dy, y, True)
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2).requires_grad_(True)
+    wt = torch.from_numpy(w).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    bt = torch.from_numpy(b).requires_grad_(True)
+    yt = F.relu(F.conv2d(xt, wt, bias=bt, padding=1))
+    yt.backward(torch.from_numpy(dy).permute(0, 3, 1, 2))
+    assert np.allclose(db, bt.grad.numpy(), rtol=0, atol=1e-12)
+    # dz is what the convolution's own gradients take: chain it through the oracle's data and filter gradients
+    assert np.allclose(oracle.conv_bwd_data(s, dz, w), xt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
+    assert np.allclose(oracle.conv_bwd_filter(s, x, dz), wt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
