@@ -138,6 +138,19 @@ dl_status conv2d_transpose_bwd_data(const dl_conv_desc *desc, const void *dy, co
 dl_status conv2d_transpose_bwd_filter(const dl_conv_desc *desc, const void *x, const void *dy, void *dw,
                                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Backward of the point-wise tail of conv2d_fwd_bias_relu in one pass (paper, Sec.
+ * "Single GPU Performance": fewer reads and writes of the tensors by fusing
+ * point-wise operations): given dy = dL/dy and the forward output y, both
+ * [n_pixels, K] in `dtype`,
+ *   dz[i,k]  = dy[i,k] if y[i,k] > 0 else 0      (relu != 0; the tensor the
+ *              convolution's data- and filter-gradient entry points take as dy)
+ *   dbias[k] = sum_i dz[i,k]                      (device float[K], fp32 sums in a fixed order)
+ * With relu == 0 only dbias is computed (dz = dy; y and dz may be NULL).  dz may
+ * alias dy.  Workspace: dl_bias_relu_bwd_workspace_bytes(n_pixels, K). */
+dl_status dl_bias_relu_bwd_workspace_bytes(int64_t n_pixels, int32_t K, size_t *bytes);
+dl_status bias_relu_bwd(const void *dy, const void *y, int32_t dtype, int64_t n_pixels, int32_t K, int32_t relu,
+                        void *dz, float *dbias, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Scratch bytes for weighted_pixel_ce_fwd_bwd on n_pixels pixels. */
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes);
 

@@ -21,7 +21,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
-           "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
+           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
 
 
 class DlError(RuntimeError):
@@ -74,6 +74,8 @@ def _load() -> ctypes.CDLL:
                  "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter"):
         getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
     lib.conv2d_fwd_bias_relu.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+    lib.dl_bias_relu_bwd_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.bias_relu_bwd.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, sz, vp]
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
     for name in ("weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd"):
         getattr(lib, name).argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp, sz, vp]
@@ -262,6 +264,27 @@ def conv2d_transpose_bwd_filter(desc: ConvDesc, x: torch.Tensor, dy: torch.Tenso
     _check(_lib.conv2d_transpose_bwd_filter(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(dy), _dev_ptr(dw),
                                             _dev_ptr(ws), nb, _stream()), "conv2d_transpose_bwd_filter")
     return dw
+
+
+def bias_relu_bwd(dy: torch.Tensor, y: torch.Tensor | None, relu: bool, dz: torch.Tensor | None = None,
+                  dbias: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """dy, y: [..., K] fp16/bf16.  Returns (dz, dbias float32[K]); with relu False dz is dy itself."""
+    K = dy.shape[-1]
+    n = dy.numel() // K
+    if relu:
+        if y is None or y.shape != dy.shape or y.dtype != dy.dtype:
+            raise ValueError("y must match dy")
+        if dz is None:
+            dz = torch.empty_like(dy)
+    if dbias is None:
+        dbias = torch.empty(K, dtype=torch.float32, device=dy.device)
+    need = ctypes.c_size_t(0)
+    _check(_lib.dl_bias_relu_bwd_workspace_bytes(n, K, ctypes.byref(need)), "dl_bias_relu_bwd_workspace_bytes")
+    ws, nb = _workspace(int(need.value), dy.device, workspace)
+    _check(_lib.bias_relu_bwd(_dev_ptr(dy), _dev_ptr(y) if relu else None, _dtype_code(dy), n, K, 1 if relu else 0,
+                              _dev_ptr(dz) if relu else None, _dev_ptr(dbias), _dev_ptr(ws), nb, _stream()),
+           "bias_relu_bwd")
+    return (dz if relu else dy), dbias
 
 
 def weighted_pixel_ce_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,

@@ -436,6 +436,37 @@ dl_status conv2d_transpose_bwd_filter(const dl_conv_desc *d, const void *x, cons
     return conv2d_bwd_filter(d, dy, x, dw, workspace, workspace_bytes, hip_stream);
 }
 
+dl_status dl_bias_relu_bwd_workspace_bytes(int64_t n_pixels, int32_t K, size_t *bytes)
+{
+    if (!bytes) return DL_ERR_NULL;
+    if (n_pixels < 0 || K < 1 || n_pixels * K >= MAX_ELEMS) return DL_ERR_SHAPE;
+    *bytes = (size_t)dlk::tail_bwd_blocks(n_pixels, K) * K * sizeof(float);
+    return DL_OK;
+}
+
+dl_status bias_relu_bwd(const void *dy, const void *y, int32_t dtype, int64_t n_pixels, int32_t K, int32_t relu,
+                        void *dz, float *dbias, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!dbias) return DL_ERR_NULL;
+    if (n_pixels < 0 || K < 1 || n_pixels * K >= MAX_ELEMS) return DL_ERR_SHAPE;
+    if (n_pixels > 0 && (!dy || (relu && (!y || !dz)))) return DL_ERR_NULL;
+    if (dtype != DL_F16 && dtype != DL_BF16) return DL_ERR_DTYPE;
+    if (!aligned16(dy) || !aligned16(y) || !aligned16(dz) || (reinterpret_cast<uintptr_t>(dbias) & 3u)) return DL_ERR_ALIGN;
+    const size_t need = (size_t)dlk::tail_bwd_blocks(n_pixels, K) * K * sizeof(float);
+    if (!workspace || workspace_bytes < need) return DL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DL_ERR_ALIGN;
+    dlk::TailBwdArgs a{};
+    a.dy = static_cast<const uint16_t *>(dy);
+    a.y = static_cast<const uint16_t *>(y);
+    a.dz = static_cast<uint16_t *>(dz);
+    a.partial = static_cast<float *>(workspace);
+    a.dbias = dbias;
+    a.npix = n_pixels;
+    a.K = K;
+    a.relu = relu ? 1 : 0;
+    return hip_status(dlk::launch_tail_bwd(a, dtype == DL_BF16, static_cast<hipStream_t>(hip_stream)));
+}
+
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes)
 {
     if (!bytes) return DL_ERR_NULL;

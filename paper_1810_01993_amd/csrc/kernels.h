@@ -170,6 +170,18 @@ hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n,
 hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                      const float *bias, int32_t relu, int32_t ncols, hipStream_t stream);
 
+// Backward of the point-wise tail y = max(s + bias, 0): dz = dy masked by y > 0 (relu != 0;
+// otherwise dz and y are not touched), dbias = column sums of dz.  partial: blocks x K floats.
+struct TailBwdArgs {
+    const uint16_t *dy, *y;     // [npix][K]
+    uint16_t *dz;
+    float *partial, *dbias;
+    int64_t npix, chunk;        // chunk: pixels per workgroup (set by the launcher)
+    int32_t K, relu;
+};
+int tail_bwd_blocks(int64_t npix, int K);
+hipError_t launch_tail_bwd(const TailBwdArgs &a, bool is_bf16, hipStream_t stream);
+
 // Weighted per-pixel cross-entropy, 3 classes.
 int ce_num_blocks(int64_t n_pixels);
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,

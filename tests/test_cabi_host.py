@@ -84,4 +84,9 @@ def test_pointer_checks_happen_before_any_launch(api):
         assert fn(ref, 16, 16, 24, None, 0, None) == 4
     assert lib.conv2d_fwd_bias_relu(ref, None, 16, None, 1, 16, None, 0, None) == 1
     assert lib.conv2d_fwd_bias_relu(ref, 16, 16, 18, 1, 16, None, 0, None) == 4                    # bias not 4-byte aligned
+    assert lib.bias_relu_bwd(16, 16, 0, 8, 8, 1, 16, None, 16, 4096, None) == 1            # no dbias
+    assert lib.bias_relu_bwd(16, None, 0, 8, 8, 1, 16, 16, 16, 4096, None) == 1            # ReLU needs y
+    assert lib.bias_relu_bwd(16, 16, 2, 8, 8, 1, 16, 16, 16, 4096, None) == 3
+    assert lib.bias_relu_bwd(16, 16, 0, 8, 0, 1, 16, 16, 16, 4096, None) == 2
+    assert lib.bias_relu_bwd(16, 16, 0, 8, 8, 1, 16, 16, None, 0, None) == 5
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)
