@@ -151,6 +151,30 @@ dl_status dl_bias_relu_bwd_workspace_bytes(int64_t n_pixels, int32_t K, size_t *
 dl_status bias_relu_bwd(const void *dy, const void *y, int32_t dtype, int64_t n_pixels, int32_t K, int32_t relu,
                         void *dz, float *dbias, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* LARC weight update for a list of layers (paper, Sec. "LARC": a separate learning
+ * rate for every layer, the size of the update defined relative to the norm of
+ * the layer's weights; the paper does not print the formula: this is the published
+ * layer-wise rate with LARC's clipping on SGD with momentum and weight decay).
+ * Per tensor, norms over the whole tensor in fp32:
+ *   local = trust * ||w|| / (||g|| + weight_decay * ||w|| + eps)   (lr if either norm is 0)
+ *   rate  = clip ? min(local, lr) : local * lr
+ *   v <- momentum * v + rate * (g + weight_decay * w);   w <- w - v
+ * tensors: HOST array of n_tensors entries; w, v: device fp32 (v may be NULL when
+ * momentum == 0 and is then not kept), g: device tensor of grad_dtype (F16, BF16 or
+ * F32: what conv2d_bwd_filter wrote), count elements each.  rates: device float[n_tensors]
+ * receiving each tensor's rate, or NULL.  Two launches per 64 tensors; results do not
+ * depend on timing.  Workspace: dl_larc_workspace_bytes(n_tensors). */
+typedef struct {
+    void *w;
+    const void *g;
+    void *v;
+    int64_t count;
+} dl_larc_tensor;
+dl_status dl_larc_workspace_bytes(int32_t n_tensors, size_t *bytes);
+dl_status larc_sgd_step(const dl_larc_tensor *tensors, int32_t n_tensors, int32_t grad_dtype, float lr, float trust,
+                        float weight_decay, float momentum, float eps, int32_t clip, float *rates,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Scratch bytes for weighted_pixel_ce_fwd_bwd on n_pixels pixels. */
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes);
 

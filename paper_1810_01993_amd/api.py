@@ -21,7 +21,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
-           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
+           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
 
 
 class DlError(RuntimeError):
@@ -76,6 +76,9 @@ def _load() -> ctypes.CDLL:
     lib.conv2d_fwd_bias_relu.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
     lib.dl_bias_relu_bwd_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.bias_relu_bwd.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, sz, vp]
+    lib.dl_larc_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.larc_sgd_step.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                  ctypes.c_float, ctypes.c_float, ctypes.c_int32, vp, vp, sz, vp]
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
     for name in ("weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd"):
         getattr(lib, name).argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp, sz, vp]
@@ -285,6 +288,40 @@ def bias_relu_bwd(dy: torch.Tensor, y: torch.Tensor | None, relu: bool, dz: torc
                               _dev_ptr(dz) if relu else None, _dev_ptr(dbias), _dev_ptr(ws), nb, _stream()),
            "bias_relu_bwd")
     return (dz if relu else dy), dbias
+
+
+class _LarcTensor(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("v", ctypes.c_void_p), ("count", ctypes.c_int64)]
+
+
+def larc_sgd_step(weights, grads, momenta, lr: float, trust: float, weight_decay: float = 0.0, momentum: float = 0.0,
+                  eps: float = 0.0, clip: bool = True, rates: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None):
+    """In-place LARC update of the fp32 tensors in ``weights`` (and ``momenta`` if momentum != 0) from
+    ``grads`` (all fp16, all bf16 or all fp32).  Returns the per-tensor rates (float32[n], device)."""
+    n = len(weights)
+    if len(grads) != n or (momentum != 0.0 and (momenta is None or len(momenta) != n)):
+        raise ValueError("one gradient (and momentum buffer) per weight tensor")
+    gd = {torch.float16: DL_F16, torch.bfloat16: DL_BF16, torch.float32: DL_F32}[grads[0].dtype] if n else DL_F32
+    table = (_LarcTensor * max(n, 1))()
+    for i in range(n):
+        w, g = weights[i], grads[i]
+        if w.dtype != torch.float32 or g.dtype != grads[0].dtype or g.numel() != w.numel():
+            raise ValueError("fp32 weights and gradients of one dtype and matching sizes required")
+        v = momenta[i] if momentum != 0.0 else None
+        if v is not None and (v.dtype != torch.float32 or v.numel() != w.numel()):
+            raise ValueError("fp32 momentum buffer of the weight's size required")
+        table[i] = _LarcTensor(_dev_ptr(w), _dev_ptr(g), _dev_ptr(v), w.numel())
+    dev = weights[0].device if n else torch.device("cuda")
+    if rates is None:
+        rates = torch.empty(max(n, 1), dtype=torch.float32, device=dev)
+    need = ctypes.c_size_t(0)
+    _check(_lib.dl_larc_workspace_bytes(n, ctypes.byref(need)), "dl_larc_workspace_bytes")
+    ws, nb = _workspace(int(need.value), dev, workspace)
+    _check(_lib.larc_sgd_step(ctypes.cast(table, ctypes.c_void_p), n, gd, ctypes.c_float(lr), ctypes.c_float(trust),
+                              ctypes.c_float(weight_decay), ctypes.c_float(momentum), ctypes.c_float(eps),
+                              1 if clip else 0, _dev_ptr(rates), _dev_ptr(ws), nb, _stream()), "larc_sgd_step")
+    return rates[:n]
 
 
 def weighted_pixel_ce_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,

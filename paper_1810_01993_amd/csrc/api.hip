@@ -467,6 +467,51 @@ dl_status bias_relu_bwd(const void *dy, const void *y, int32_t dtype, int64_t n_
     return hip_status(dlk::launch_tail_bwd(a, dtype == DL_BF16, static_cast<hipStream_t>(hip_stream)));
 }
 
+dl_status dl_larc_workspace_bytes(int32_t n_tensors, size_t *bytes)
+{
+    if (!bytes) return DL_ERR_NULL;
+    if (n_tensors < 0) return DL_ERR_SHAPE;
+    *bytes = (size_t)n_tensors * dlk::LARC_SLICES * 2 * sizeof(float);
+    return DL_OK;
+}
+
+dl_status larc_sgd_step(const dl_larc_tensor *tensors, int32_t n_tensors, int32_t grad_dtype, float lr, float trust,
+                        float weight_decay, float momentum, float eps, int32_t clip, float *rates, void *workspace,
+                        size_t workspace_bytes, void *hip_stream)
+{
+    if (n_tensors < 0) return DL_ERR_SHAPE;
+    if (n_tensors == 0) return DL_OK;
+    if (!tensors) return DL_ERR_NULL;
+    if (grad_dtype != DL_F16 && grad_dtype != DL_BF16 && grad_dtype != DL_F32) return DL_ERR_DTYPE;
+    for (int i = 0; i < n_tensors; ++i) {
+        if (!tensors[i].w || !tensors[i].g) return DL_ERR_NULL;
+        if (tensors[i].count < 1 || tensors[i].count >= MAX_ELEMS) return DL_ERR_SHAPE;
+        if ((reinterpret_cast<uintptr_t>(tensors[i].w) & 3u) || (reinterpret_cast<uintptr_t>(tensors[i].v) & 3u) ||
+            (reinterpret_cast<uintptr_t>(tensors[i].g) & (grad_dtype == DL_F32 ? 3u : 1u)))
+            return DL_ERR_ALIGN;
+        if (momentum != 0.f && !tensors[i].v) return DL_ERR_NULL;
+    }
+    const size_t need = (size_t)n_tensors * dlk::LARC_SLICES * 2 * sizeof(float);
+    if (!workspace || workspace_bytes < need) return DL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DL_ERR_ALIGN;
+    for (int first = 0; first < n_tensors; first += dlk::LARC_MAX) {
+        dlk::LarcBatch b{};
+        b.n = n_tensors - first < dlk::LARC_MAX ? n_tensors - first : dlk::LARC_MAX;
+        for (int i = 0; i < b.n; ++i) {
+            const dl_larc_tensor &t = tensors[first + i];
+            b.t[i] = dlk::LarcTensor{static_cast<float *>(t.w), t.g, momentum != 0.f ? static_cast<float *>(t.v) : nullptr,
+                                     t.count};
+        }
+        b.partial = static_cast<float *>(workspace);
+        b.rates = rates;
+        b.lr = lr; b.trust = trust; b.wd = weight_decay; b.momentum = momentum; b.eps = eps;
+        b.clip = clip ? 1 : 0;
+        b.first = first;
+        if (dlk::launch_larc(b, grad_dtype, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return DL_ERR_LAUNCH;
+    }
+    return DL_OK;
+}
+
 dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes)
 {
     if (!bytes) return DL_ERR_NULL;

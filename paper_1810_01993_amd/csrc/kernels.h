@@ -182,6 +182,18 @@ struct TailBwdArgs {
 int tail_bwd_blocks(int64_t npix, int K);
 hipError_t launch_tail_bwd(const TailBwdArgs &a, bool is_bf16, hipStream_t stream);
 
+// LARC update of up to LARC_MAX tensors (see larc.hip).  partial: 2 * LARC_SLICES floats per tensor
+// of the whole call; first: index of t[0] among the call's tensors; rates: per-tensor rate out, or null.
+constexpr int LARC_MAX = 64, LARC_SLICES = 256;
+struct LarcTensor { float *w; const void *g; float *v; int64_t count; };
+struct LarcBatch {
+    LarcTensor t[LARC_MAX];
+    float *partial, *rates;
+    float lr, trust, wd, momentum, eps;
+    int32_t clip, n, first;
+};
+hipError_t launch_larc(const LarcBatch &b, int grad_dtype, hipStream_t stream);
+
 // Weighted per-pixel cross-entropy, 3 classes.
 int ce_num_blocks(int64_t n_pixels);
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,

@@ -89,4 +89,12 @@ def test_pointer_checks_happen_before_any_launch(api):
     assert lib.bias_relu_bwd(16, 16, 2, 8, 8, 1, 16, 16, 16, 4096, None) == 3
     assert lib.bias_relu_bwd(16, 16, 0, 8, 0, 1, 16, 16, 16, 4096, None) == 2
     assert lib.bias_relu_bwd(16, 16, 0, 8, 8, 1, 16, 16, None, 0, None) == 5
+    t = (api._LarcTensor * 2)(api._LarcTensor(16, 16, None, 8), api._LarcTensor(16, None, None, 8))
+    tp = ctypes.cast(t, ctypes.c_void_p)
+    f = ctypes.c_float
+    assert lib.larc_sgd_step(tp, 2, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, 16, 1 << 20, None) == 1   # tensor 1 has no gradient
+    assert lib.larc_sgd_step(tp, 1, 0, f(.1), f(.02), f(0), f(.9), f(0), 1, None, 16, 1 << 20, None) == 1  # momentum needs v
+    assert lib.larc_sgd_step(tp, 1, 7, f(.1), f(.02), f(0), f(0), f(0), 1, None, 16, 1 << 20, None) == 3
+    assert lib.larc_sgd_step(tp, 1, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, 16, 8, None) == 5
+    assert lib.larc_sgd_step(None, 0, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, None, 0, None) == 0     # nothing to do
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)
