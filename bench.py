@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", default="f16", choices=("f16", "bf16"),
+                    help="storage type of the tensors (the headline configuration is f16; accumulation is fp32 either way)")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
     ap.add_argument("--deconv-table", action="store_true",
                     help="instead of the step: time the decoder's transposed-convolution layers (forward, data "
@@ -63,8 +65,8 @@ def device_inputs(layer, dtype, seed, torch):
     g.manual_seed(seed)
     xs = (layer.N, layer.H, layer.W, layer.C)
     if layer.name == "stem7x7":
-        _, bits = synth.quantize(synth.smooth_fields(seed, *xs), "f16")
-        x = torch.from_numpy(bits.view(np.int16)).view(torch.float16).cuda()
+        _, bits = synth.quantize(synth.smooth_fields(seed, *xs), "bf16" if dtype == torch.bfloat16 else "f16")
+        x = torch.from_numpy(bits.view(np.int16)).view(dtype).cuda()
     else:
         x = torch.randn(xs, generator=g, device="cuda", dtype=torch.float32).abs_().to(dtype)
     sigma = float(np.sqrt(2.0 / (layer.R * layer.S * layer.C)))
@@ -76,10 +78,10 @@ def device_inputs(layer, dtype, seed, torch):
 class LayerState:
     """Device buffers of one occurrence of one layer shape."""
 
-    def __init__(self, api, layer, seed, torch):
+    def __init__(self, api, layer, seed, torch, dtype_name="f16"):
         self.layer = layer
-        self.desc = api.desc_from_layer(layer, "f16")
-        self.x, self.w, self.dy = device_inputs(layer, torch.float16, seed, torch)
+        self.desc = api.desc_from_layer(layer, dtype_name)
+        self.x, self.w, self.dy = device_inputs(layer, torch.bfloat16 if dtype_name == "bf16" else torch.float16, seed, torch)
         self.y = torch.empty_like(self.dy)
         self.dx = torch.empty_like(self.x)
         self.dw = torch.empty_like(self.w)
@@ -213,9 +215,10 @@ def main():
     net = []
     for li, layer in enumerate(table):
         for occ in range(layer.count):
-            net.append(LayerState(api, layer, synth.seed_for(5, 100 * li + occ), torch))
+            net.append(LayerState(api, layer, synth.seed_for(5, 100 * li + occ), torch, args.dtype))
     n_pix = 2 * 768 * 1152
-    logits = torch.randn((n_pix, 3), device="cuda").to(torch.float16)
+    tdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    logits = torch.randn((n_pix, 3), device="cuda").to(tdtype)
     labels = torch.from_numpy(synth.ellipse_labels(synth.seed_for(5, 990), 2, 768, 1152).ravel()).cuda()
     cw = torch.tensor(synth.CLASS_WEIGHTS, dtype=torch.float32, device="cuda")
     dlogits = torch.empty_like(logits)
@@ -347,9 +350,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16",
+        "dtype": args.dtype,
         "data": "synthetic",
-        "config": {"workload": "config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, fp16 in / fp32 accumulate",
+        "config": {"workload": f"config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, {'bf16' if args.dtype == 'bf16' else 'fp16'} in / fp32 accumulate",
                    "streams": args.streams,
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
@@ -357,7 +360,7 @@ def main():
                    "loss_hbm_resident": loss_big},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": read_traffic(args.traffic_file),
-                     "kernel": "igemm_halo3x3_kernel<F16, 4>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
+                     "kernel": f"igemm_halo3x3_kernel<{'BF16' if args.dtype == 'bf16' else 'F16'}, 4>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
                      "launches_per_step": dom_n,
                      "avg_launch_ms": dom_ms / dom_n, "flop_per_launch": dom_flops / dom_n},
     }
