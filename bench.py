@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--dtype", default="f16", choices=("f16", "bf16"),
                     help="storage type of the tensors (the headline configuration is f16; accumulation is fp32 either way)")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
+    ap.add_argument("--tiramisu-table", action="store_true",
+                    help="per-layer times at the layer shapes of the paper's second network (modified Tiramisu); "
+                         "not part of the headline step")
     ap.add_argument("--deconv-table", action="store_true",
                     help="instead of the step: time the decoder's transposed-convolution layers (forward, data "
                          "gradient, filter gradient each) and print a table; no JSON line")
@@ -194,6 +197,70 @@ def deconv_table(args):
             print(f"{layer.name:34s} {name:28s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f}", flush=True)
 
 
+def tiramisu_table(args):
+    """Every layer shape of the paper's second network (layers.tiramisu_layers: growth 32, 5x5), N=2, fp16:
+    HIP-event time of each pass, median over --steps calls after --warmup; the three passes of all layers
+    are summed at the end (one stream, no overlap: an upper bound of the convolution time of a step)."""
+    import torch
+    from paper_1810_01993_amd import api, layers
+
+    torch.cuda.set_device(0)
+    convs, deconvs = layers.tiramisu_layers(2, 768, 1152)
+    print(f"{'layer':34s} {'pass':8s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s}")
+    total_ms, total_flop = 0.0, 0.0
+    for li, layer in enumerate(convs + deconvs):
+        transposed = li >= len(convs)
+        desc = api.desc_from_layer(layer, "f16")
+        g = torch.Generator(device="cuda")
+        g.manual_seed(2000 + li)
+        sigma = float(np.sqrt(2.0 / (layer.R * layer.S * (layer.K if transposed else layer.C))))
+        w = (torch.randn((layer.K, layer.R, layer.S, layer.C), generator=g, device="cuda") * sigma).half()
+        big = torch.randn((layer.N, layer.H, layer.W, layer.C), generator=g, device="cuda")       # the conv's input side
+        small = torch.randn((layer.N, layer.P, layer.Q, layer.K), generator=g, device="cuda")     # the conv's output side
+        if transposed:
+            x, dy = small.abs_().half(), big.half()                # layer input [N,P,Q,K], output gradient [N,H,W,C]
+            y, dx = torch.empty_like(dy), torch.empty_like(x)
+        else:
+            x, dy = big.abs_().half(), small.half()
+            y, dx = torch.empty_like(dy), torch.empty_like(x)
+        del big, small
+        dw = torch.empty_like(w)
+        ws = torch.empty(max(16, max(api.dl_conv_workspace_bytes(desc, p) for p in range(3))), dtype=torch.uint8,
+                         device="cuda")
+        if transposed:
+            calls = {"fwd": lambda: api.conv2d_transpose_fwd(desc, x, w, y=y, workspace=ws),
+                     "dgrad": lambda: api.conv2d_transpose_bwd_data(desc, dy, w, dx=dx, workspace=ws),
+                     "wgrad": lambda: api.conv2d_transpose_bwd_filter(desc, x, dy, dw=dw, workspace=ws)}
+        else:
+            calls = {"fwd": lambda: api.conv2d_fwd(desc, x, w, y=y, workspace=ws),
+                     "dgrad": lambda: api.conv2d_bwd_data(desc, dy, w, dx=dx, workspace=ws),
+                     "wgrad": lambda: api.conv2d_bwd_filter(desc, x, dy, dw=dw, workspace=ws)}
+        min_bytes = 2.0 * (x.numel() + w.numel() + dy.numel())
+        for name, fn in calls.items():
+            for _ in range(args.warmup):
+                fn()
+            ts = []
+            for _ in range(args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            ms = float(np.median(ts))
+            tf = layer.flops() / (ms * 1e-3) / 1e12
+            gbs = min_bytes / (ms * 1e-3) / 1e9
+            total_ms += ms
+            total_flop += layer.flops()
+            print(f"{layer.name:34s} {name:8s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
+                  f"{100 * gbs / HBM_PEAK_GBS:6.1f}", flush=True)
+        del x, dy, y, dx, w, dw, ws
+        torch.cuda.empty_cache()
+    print(f"sum of the three passes of all {len(convs) + len(deconvs)} layers: {total_ms:.3f} ms, "
+          f"{total_flop / 1e12:.2f} TFLOP, {total_flop / (total_ms * 1e-3) / 1e12:.1f} TFLOP/s "
+          f"({2 / (total_ms * 1e-3):.1f} samples/s for the convolutions alone)")
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -208,6 +275,9 @@ def main():
     torch.cuda.set_device(0)
     if args.deconv_table:
         deconv_table(args)
+        return
+    if args.tiramisu_table:
+        tiramisu_table(args)
         return
     _, table = layers.config5()
 

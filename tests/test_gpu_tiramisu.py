@@ -1,0 +1,74 @@
+"""GPU parity at the layer shapes of the paper's second network (the modified
+Tiramisu: growth rate 32, 5x5 convolutions, stride-2 1x1 transitions down,
+stride-2 3x3 transposed convolutions up; ``layers.tiramisu_layers``) against
+the fp64 oracle: scaled-down copies element by element, the real sizes on
+sampled outputs."""
+import pytest
+import torch
+
+from paper_1810_01993_amd import layers, synth
+from paper_1810_01993_amd.layers import ConvLayer
+
+from test_gpu_conv import check_layer
+from test_gpu_conv_transpose import check_transpose
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1810_01993_amd import api as _api
+    assert torch.cuda.is_available(), "a GPU is required for -m gpu tests"
+    return _api
+
+
+CONVS, DECONVS = layers.tiramisu_layers(2, 768, 1152)
+
+
+L = ConvLayer
+# the real channel counts on small, ragged maps: several tiles in each direction, partial last 32-channel chunk
+SMALL = [
+    L("tira.small.5x5.48-32", 2, 23, 37, 48, 32, 5, 5, 1, 2, 1),
+    L("tira.small.5x5.80-32", 1, 40, 70, 80, 32, 5, 5, 1, 2, 1),
+    L("tira.small.5x5.208-32", 1, 33, 45, 208, 32, 5, 5, 1, 2, 1),
+    L("tira.small.5x5.624-32", 2, 12, 18, 624, 32, 5, 5, 1, 2, 1),
+    L("tira.small.5x5.map-smaller-than-filter", 1, 3, 4, 112, 32, 5, 5, 1, 2, 1),
+    L("tira.small.td.1x1.s2.112", 2, 22, 34, 112, 112, 1, 1, 2, 0, 1),
+    L("tira.small.td.1x1.s2.368.odd-map", 1, 21, 27, 368, 368, 1, 1, 2, 0, 1),
+    L("tira.small.first.3x3.16-48", 1, 30, 41, 16, 48, 3, 3, 1, 1, 1),
+    L("tira.small.logits.240-3", 1, 31, 29, 240, 3, 1, 1, 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("layer", SMALL, ids=[l.name for l in SMALL])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_small_copies(api, layer, dtype):
+    check_layer(api, layer, dtype, synth.seed_for(6, 10 * SMALL.index(layer) + (dtype == "bf16")))
+
+
+@pytest.mark.parametrize("layer,dtype", [(L("tira.small.tu.3x3.s2.64", 1, 40, 56, 64, 64, 3, 3, 2, 1, 1), "f16"),
+                                         (L("tira.small.tu.3x3.s2.160", 2, 24, 36, 160, 160, 3, 3, 2, 1, 1), "bf16")],
+                         ids=["tu64", "tu160"])
+def test_small_transitions_up(api, layer, dtype):
+    check_transpose(api, layer, dtype, synth.seed_for(6, 200 + layer.C))
+
+
+# one layer of every resolution at its real size (sampled outputs), fp16; the two full-resolution ones carry
+# most of the network's FLOPs
+FULL = [l for l in CONVS if l.name in ("tira.first.3x3", "tira.down1.5x5.80-32", "tira.up1.5x5.208-32", "tira.td1.1x1.s2.112",
+                                       "tira.up2.5x5.272-32", "tira.up3.5x5.400-32", "tira.up4.5x5.624-32",
+                                       "tira.down5.5x5.496-32", "tira.td4.1x1.s2.368", "tira.logits.1x1")]
+
+
+@pytest.mark.parametrize("layer", FULL, ids=[l.name for l in FULL])
+def test_full_size_layers(api, layer):
+    big = layer.H * layer.W * layer.N * max(layer.C, layer.K) > 2e8
+    check_layer(api, layer, "f16", synth.seed_for(6, 300 + FULL.index(layer)), n_samples=8192 if big else 4096)
+    torch.cuda.empty_cache()
+
+
+def test_full_size_transition_up(api):
+    layer = DECONVS[-1]                                      # 64 -> 64, 384x576 -> 768x1152
+    assert (layer.H, layer.W, layer.P, layer.Q) == (768, 1152, 384, 576)
+    check_transpose(api, layer, "f16", synth.seed_for(6, 400), n_samples=3000)
+    torch.cuda.empty_cache()
