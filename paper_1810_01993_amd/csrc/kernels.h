@@ -76,6 +76,10 @@ hipError_t launch_igemm_dma(const IgemmArgs &a, bool is_bf16, int cfg, hipStream
 // Halo-tile variant for stride-1 multi-tap filters.  a.B must point at the
 // blocked filter copy [chunk][tap][a.Nout][32] made by launch_filter_block.
 int igemm_halo_columns(const IgemmArgs &a);
+// Dense 5x5, unit stride and dilation, forward-oriented taps, 8..32 output columns (a multiple of 8), D 16-byte
+// aligned: one 32-wide column tile per 16 x 32 pixel patch; a.B as for the other halo-tile kernels.
+bool igemm_narrow5x5_applicable(const IgemmArgs &a);
+hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 bool igemm_halo3x3_applicable(const IgemmArgs &a);
 int64_t igemm_halo3x3_tiles(const IgemmArgs &a);
 hipError_t launch_igemm_halo3x3(const IgemmArgs &a, bool is_bf16, hipStream_t stream);

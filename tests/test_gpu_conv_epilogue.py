@@ -71,6 +71,8 @@ CASES = [
     (L("e.logits.k3", 1, 33, 47, 256, 3, 1, 1, 1, 0, 1), "bf16"),
     (L("e.thin.c4", 1, 40, 50, 4, 64, 1, 1, 1, 0, 1), "f16"),                     # 4 input channels: the streaming kernel
     (L("e.stem7x7", 2, 30, 44, 16, 64, 7, 7, 2, 3, 1), "bf16"),
+    (L("e.narrow5x5.k32", 4, 75, 200, 16, 32, 5, 5, 1, 2, 1), "f16"),             # 5x5 kernel for <= 32 output channels
+    (L("e.narrow5x5.k24", 3, 100, 230, 40, 24, 5, 5, 1, 2, 1), "bf16"),
 ]
 
 

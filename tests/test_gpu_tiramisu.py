@@ -46,6 +46,22 @@ def test_small_copies(api, layer, dtype):
     check_layer(api, layer, dtype, synth.seed_for(6, 10 * SMALL.index(layer) + (dtype == "bf16")))
 
 
+# enough patches (>= 128) for the 5x5 kernel with at most 32 output channels: ragged in both directions, a partial
+# 32-channel chunk, fewer than 32 output channels, a map that needs other padding; the first one element by element
+NARROW = [
+    (L("tira.narrow.c16", 4, 75, 200, 16, 32, 5, 5, 1, 2, 1), "f16"),
+    (L("tira.narrow.c16.bf16", 4, 75, 200, 16, 32, 5, 5, 1, 2, 1), "bf16"),
+    (L("tira.narrow.c72.k24", 3, 100, 230, 72, 24, 5, 5, 1, 2, 1), "f16"),
+    (L("tira.narrow.c48.pad1", 2, 130, 260, 48, 32, 5, 5, 1, 1, 1), "bf16"),       # output 128 x 258
+    (L("tira.narrow.c8.k8.pad4", 2, 120, 250, 8, 8, 5, 5, 1, 4, 1), "f16"),        # output 124 x 254, taps deep in the padding
+]
+
+
+@pytest.mark.parametrize("layer,dtype", NARROW, ids=[l.name for l, _ in NARROW])
+def test_narrow_5x5_kernel(api, layer, dtype):
+    check_layer(api, layer, dtype, synth.seed_for(6, 100 + NARROW.index((layer, dtype))), passes=("fwd",))
+
+
 @pytest.mark.parametrize("layer,dtype", [(L("tira.small.tu.3x3.s2.64", 1, 40, 56, 64, 64, 3, 3, 2, 1, 1), "f16"),
                                          (L("tira.small.tu.3x3.s2.160", 2, 24, 36, 160, 160, 3, 3, 2, 1, 1), "bf16")],
                          ids=["tu64", "tu160"])
