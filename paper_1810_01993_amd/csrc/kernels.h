@@ -160,6 +160,11 @@ struct Wgrad3x3Plan { int slices, rs, xs; };
 bool wgrad3x3_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw);
 Wgrad3x3Plan wgrad3x3_make_plan(int N, int H, int W, int C, int K);
 hipError_t launch_wgrad3x3(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream);
+// The same for dense 5x5, stride 1, padding 2 with at most 32 output channels (same argument and plan structs;
+// partial sums [slice][K][5][5][C]).
+bool wgrad5x5_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw);
+Wgrad3x3Plan wgrad5x5_make_plan(int N, int H, int W, int C, int K);
+hipError_t launch_wgrad5x5(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream);
 
 // Streaming kernels for 1x1 layers with <= 4 channels on one side (cfg -2 of the plan).
 bool thin_rows_applicable(const IgemmArgs &a);

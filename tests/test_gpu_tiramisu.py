@@ -58,8 +58,19 @@ NARROW = [
 
 
 @pytest.mark.parametrize("layer,dtype", NARROW, ids=[l.name for l, _ in NARROW])
-def test_narrow_5x5_kernel(api, layer, dtype):
-    check_layer(api, layer, dtype, synth.seed_for(6, 100 + NARROW.index((layer, dtype))), passes=("fwd",))
+def test_narrow_5x5_kernels(api, layer, dtype):
+    """Forward kernel for at most 32 output channels and (padding 2) the fused-tap filter-gradient kernel."""
+    check_layer(api, layer, dtype, synth.seed_for(6, 100 + NARROW.index((layer, dtype))), passes=("fwd", "wgrad"))
+
+
+def test_filter_gradient_5x5_slices_and_edges(api):
+    """The 5x5 filter-gradient kernel where its slicing shows: a map whose width is not a multiple of the
+    32-pixel strip and whose height does not divide into equal row ranges, 3 images, a partial channel block
+    (C = 40), 8 output channels; element by element."""
+    layer = L("tira.wgrad.ragged", 3, 67, 91, 40, 8, 5, 5, 1, 2, 1)
+    check_layer(api, layer, "f16", synth.seed_for(6, 150), passes=("wgrad",))
+    layer = L("tira.wgrad.fp32-out", 1, 150, 160, 16, 32, 5, 5, 1, 2, 1)
+    check_layer(api, layer, "bf16", synth.seed_for(6, 151), passes=("wgrad",), dw_f32=True)
 
 
 @pytest.mark.parametrize("layer,dtype", [(L("tira.small.tu.3x3.s2.64", 1, 40, 56, 64, 64, 3, 3, 2, 1, 1), "f16"),
