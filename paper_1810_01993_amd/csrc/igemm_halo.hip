@@ -258,6 +258,7 @@ static int halo_mode()
 
 static bool use_3x3(const IgemmArgs &a) { return halo_mode() == 1 && igemm_halo3x3_applicable(a); }
 static bool use_narrow(const IgemmArgs &a) { return halo_mode() == 1 && igemm_narrow5x5_applicable(a); }
+static bool use_wide(const IgemmArgs &a) { return halo_mode() == 1 && igemm_wide5x5_applicable(a); }
 
 // Can a halo-tile kernel take all a.Nout columns?
 static bool halo_takes(const IgemmArgs &a)
@@ -280,7 +281,7 @@ static bool halo_takes(const IgemmArgs &a)
 int igemm_halo_columns(const IgemmArgs &a)
 {
     if (!halo_mode()) return 0;
-    if (use_narrow(a)) return a.Nout;                   // 5x5 with at most 32 columns: its own kernel
+    if (use_narrow(a) || use_wide(a)) return a.Nout;     // 5x5 with at most 32 columns or 32 reduction channels: own kernels
     IgemmArgs h = a;
     if (!use_3x3(a)) {
         const int rem = a.Nout % HALO_BN;
@@ -297,6 +298,7 @@ size_t igemm_blocked_filter_bytes(const IgemmArgs &a)
 hipError_t launch_igemm_halo(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
 {
     if (use_narrow(a)) return launch_igemm_narrow5x5(a, is_bf16, stream);
+    if (use_wide(a)) return launch_igemm_wide5x5(a, is_bf16, stream);
     const int64_t tiles = (int64_t)a.NB * ((a.OH + HALO_TH - 1) / HALO_TH) * ((a.OW + HALO_TW - 1) / HALO_TW) *
                           ((a.Nout + HALO_BN - 1) / HALO_BN);
     if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;

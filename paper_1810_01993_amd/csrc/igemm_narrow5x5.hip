@@ -201,6 +201,162 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
     }
 }
 
+// ---- the mirror case: at most 32 INPUT channels, many output columns ------------------------
+// The data gradient of such a layer (dx of C channels from dy of 32) has a single 32-channel
+// chunk of reduction, so a tile of the kernels above would be 25 steps long and mostly set-up.
+// Here a workgroup (4 waves, wave w = patch rows 4w .. 4w+3) deposits the halo image of its
+// 16 x 32 patch once and then produces ALL output columns, 64 at a time: per column tile 25
+// steps (one tap each, 4 KB of filter through a ring of six LDS slots, four steps in flight),
+// the 16 halo-row fragments re-read once per column shift and kept for its five row shifts,
+// 32 MFMAs per step and wave.  Blocks of 16 columns beyond the last are skipped, not padded.
+// The accumulators go straight to memory (a lane holds four consecutive channels of a pixel:
+// 8-byte stores; the four blocks of a pixel complete a 128-byte line in L2).
+// Taps may be mirrored (data gradient) or not.
+template <class T>
+__global__ __launch_bounds__(256, 2) void igemm_wide5x5_kernel(const IgemmArgs p)
+{
+    constexpr int NW = 4, TM = 4, KB = 4, BN = KB * 16;
+    constexpr int HW = N5_HW, HH = N5_HH;
+    constexpr int HPIECES = (HH * HW + 15) / 16;         // 45 pieces of 16 halo pixels
+    constexpr int AW = (HPIECES + NW - 1) / NW;          // halo loads per wave (stand-ins included)
+    constexpr int S = 6, IN_FLIGHT = S - 2;              // filter ring; one load per wave per step
+    constexpr int H_ELEMS = HPIECES * 16 * BK, F_ELEMS = BN * BK, SPARE_ELEMS = NW * 16 * BK;
+    __shared__ __align__(16) uint16_t lds[H_ELEMS + S * F_ELEMS + SPARE_ELEMS];
+    uint16_t *const sH = lds, *const sF = lds + H_ELEMS, *const sSpare = sF + S * F_ELEMS;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool flip_r = p.dth < 0, flip_s = p.dtw < 0;   // which tap a given shift belongs to
+    const int oy_min = flip_r ? p.th0 - (N5_T - 1) : p.th0, ox_min = flip_s ? p.tw0 - (N5_T - 1) : p.tw0;
+
+    const int tiles_x = (p.OW + N5_PW - 1) / N5_PW, tiles_y = (p.OH + N5_PH - 1) / N5_PH;
+    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int tx = tile % tiles_x; tile /= tiles_x;
+    const int ty = tile % tiles_y;
+    const int img = tile / tiles_y;
+    const int y0 = ty * N5_PH, x0 = tx * N5_PW;
+    const int ntiles_n = (p.Nout + BN - 1) / BN;
+
+    const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
+    const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)(N5_T * N5_T) * p.Nout * BK * 2u);
+
+    const int lrow = lane >> 2;
+    const int lane_c = ((lane & 3) ^ n5_swz(lrow)) * 8;
+    // ---- the halo image, once -------------------------------------------------------
+#pragma unroll
+    for (int a = 0; a < AW; ++a) {
+        const int pc = wave + a * NW;
+        const int hp = pc * 16 + lrow;
+        const int hy = hp / HW, hx = hp - hy * HW;
+        const int iy = y0 + oy_min + hy, ix = x0 + ox_min + hx;
+        const bool ok = pc < HPIECES && hy < HH && (unsigned)iy < (unsigned)p.IH && (unsigned)ix < (unsigned)p.IW && lane_c < p.Cin;
+        const uint32_t dst = pc < HPIECES ? lds_addr(sH) + pc * 16 * BK * 2 : lds_addr(sSpare) + wave * 16 * BK * 2;
+        dma_load_16B(rsA, dst, ok ? (uint32_t)(((img * p.IH + iy) * p.IW + ix) * p.Cin + lane_c) * 2u : OOB_OFFSET);
+    }
+    // ---- the filter stream: step g = (column tile, column shift, row shift) -----------------
+    // this wave's piece of a tap tile: rows (output columns) 16*wave + lrow of the column tile
+    int ld_ct = 0, ld_cs = 0, ld_tr = 0;
+    auto issue_filter = [&](int slot) {
+        const int jr = flip_r ? N5_T - 1 - ld_tr : ld_tr, js = flip_s ? N5_T - 1 - ld_cs : ld_cs;
+        const int j = ld_ct * BN + 16 * wave + lrow;
+        const bool ok = ld_ct < ntiles_n && j < p.Nout;
+        dma_load_16B(rsB, lds_addr(sF + slot * F_ELEMS) + wave * 16 * BK * 2,
+                     ok ? (uint32_t)(((jr * N5_T + js) * p.Nout + j) * BK + lane_c) * 2u : OOB_OFFSET);
+        if (++ld_tr == N5_T) {
+            ld_tr = 0;
+            if (++ld_cs == N5_T) { ld_cs = 0; ++ld_ct; }
+        }
+    };
+
+    floatx4_t acc[TM][KB][2];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[i][kb][b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    };
+    clear_acc();
+
+    const int frow = lane & 15, fsl = lane >> 4;
+    const int foff = frow * BK + ((fsl ^ n5_swz(frow)) << 3);
+    const int hbase = (wave * TM) * HW + frow;
+    const bool tail = p.bias != nullptr || p.relu != 0;
+
+#pragma unroll
+    for (int k = 0; k < S - 1; ++k) issue_filter(k);
+    int slot = 0;
+    for (int ct = 0; ct < ntiles_n; ++ct) {
+        const int nblk = min(KB, (p.Nout - ct * BN + 15) / 16);     // 16-column blocks of this tile that exist
+#pragma unroll
+        for (int cs = 0; cs < N5_T; ++cs) {
+            u32x4_t fa[TM + N5_T - 1][2];
+#pragma unroll
+            for (int tr = 0; tr < N5_T; ++tr) {
+                // this wave's load for the step has landed (four later ones may be in flight); after the
+                // barrier everybody's has, and every wave is past its reads of the previous step's slot
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT) : "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                issue_filter(slot == 0 ? S - 1 : slot - 1);
+                if (tr == 0) {
+                    // (from opaque copies, so that the 40 fragment addresses of a column tile are computed
+                    // here, 8 at a time, and not kept in registers across the whole loop)
+                    int hb = hbase, sl = fsl;
+                    asm volatile("" : "+v"(hb), "+v"(sl));
+#pragma unroll
+                    for (int r = 0; r < TM + N5_T - 1; ++r)
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            const int h = hb + r * HW + cs + 16 * b;
+                            fa[r][b] = *reinterpret_cast<const u32x4_t *>(sH + h * BK + ((sl ^ n5_swz(h)) << 3));
+                        }
+                }
+                u32x4_t fb[KB];
+                const uint16_t *wb = sF + slot * F_ELEMS + foff;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) fb[kb] = *reinterpret_cast<const u32x4_t *>(wb + kb * 16 * BK);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+                    if (kb < nblk) {
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int b = 0; b < 2; ++b) T::mfma16_acc(acc[i][kb][b], fb[kb], fa[i + tr][b]);   // rows = channels
+                    }
+                slot = slot + 1 == S ? 0 : slot + 1;
+            }
+        }
+        // ---- the column tile is complete: register v of lane l of a block holds channel 4*(l/16) + v of pixel l%16
+        mfma_acc_settle();
+        // (addressing from a copy of the lane number the optimiser cannot see through: computed before the
+        // loop, the eight pixel addresses would occupy registers the steps need)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int col = ct * BN + kb * 16 + 4 * (ln >> 4);
+            if (kb >= nblk || col >= p.Nout) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    floatx4_t c = acc[i][kb][b];
+                    if (tail) c = apply_tail4(c, p.bias, p.relu, col, p.Nout);
+                    const int y = y0 + wave * TM + i, x = x0 + b * 16 + (ln & 15);
+                    if (y >= p.OH || x >= p.OW) continue;
+                    u32x2_t pk;
+                    pk[0] = (uint32_t)T::from_float(c[0]) | ((uint32_t)T::from_float(c[1]) << 16);
+                    pk[1] = (uint32_t)T::from_float(c[2]) | ((uint32_t)T::from_float(c[3]) << 16);
+                    *reinterpret_cast<u32x2_t *>(p.D + ((size_t)(img * p.OH + y) * p.OW + x) * p.ldd + col) = pk;
+                }
+        }
+        clear_acc();
+    }
+    // the trailing filter loads (zeros) land before the workgroup gives its LDS back
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 static int64_t narrow_tiles(const IgemmArgs &a)
 {
     return (int64_t)a.NB * ((a.OH + N5_PH - 1) / N5_PH) * ((a.OW + N5_PW - 1) / N5_PW);
@@ -217,6 +373,27 @@ bool igemm_narrow5x5_applicable(const IgemmArgs &a)
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && a.dth == 1 && a.dtw == 1 && a.Cin % 8 == 0 &&
            a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && narrow_tiles(a) >= 128;
+}
+
+// At most 32 input channels (one chunk), any number (a multiple of 4) of output columns, taps forward or mirrored.
+bool igemm_wide5x5_applicable(const IgemmArgs &a)
+{
+    static const int mode = [] {
+        const char *e = std::getenv("DLCONV_WIDE5X5");      // tuning override: 0 = never
+        return e ? std::atoi(e) : 1;
+    }();
+    const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
+    return mode && dense && a.TR == N5_T && a.TS == N5_T && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0 &&
+           a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && narrow_tiles(a) >= 128;
+}
+
+hipError_t launch_igemm_wide5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
+{
+    const int64_t tiles = narrow_tiles(a);
+    if (!igemm_wide5x5_applicable(a) || tiles > 0x7fffffff || (reinterpret_cast<uintptr_t>(a.D) & 7) != 0) return hipErrorInvalidValue;
+    if (is_bf16) hipLaunchKernelGGL(igemm_wide5x5_kernel<BF16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(igemm_wide5x5_kernel<F16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream)

@@ -80,6 +80,10 @@ int igemm_halo_columns(const IgemmArgs &a);
 // aligned: one 32-wide column tile per 16 x 32 pixel patch; a.B as for the other halo-tile kernels.
 bool igemm_narrow5x5_applicable(const IgemmArgs &a);
 hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+// The mirror case: dense 5x5, unit stride and dilation, taps forward or mirrored, at most 32 input channels (one
+// chunk), more than 32 output columns (a multiple of 4), D 8-byte aligned: the data gradient of such a layer.
+bool igemm_wide5x5_applicable(const IgemmArgs &a);
+hipError_t launch_igemm_wide5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 bool igemm_halo3x3_applicable(const IgemmArgs &a);
 int64_t igemm_halo3x3_tiles(const IgemmArgs &a);
 hipError_t launch_igemm_halo3x3(const IgemmArgs &a, bool is_bf16, hipStream_t stream);

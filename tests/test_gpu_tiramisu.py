@@ -63,6 +63,23 @@ def test_narrow_5x5_kernels(api, layer, dtype):
     check_layer(api, layer, dtype, synth.seed_for(6, 100 + NARROW.index((layer, dtype))), passes=("fwd", "wgrad"))
 
 
+# the mirror case (at most 32 channels on the reduction side, many output columns): data gradients of the layers
+# above with more than 32 input channels, and forward passes from few to many channels
+WIDE = [
+    (L("tira.wide.dgrad.c72.k24", 3, 100, 230, 72, 24, 5, 5, 1, 2, 1), "f16", "dgrad"),      # 64 + 8 columns, 24-channel chunk
+    (L("tira.wide.dgrad.c48.pad1", 2, 130, 260, 48, 32, 5, 5, 1, 1, 1), "bf16", "dgrad"),    # three blocks of 16 columns
+    (L("tira.wide.dgrad.c208", 3, 100, 230, 208, 32, 5, 5, 1, 2, 1), "f16", "dgrad"),        # the full-resolution layer's channels
+    (L("tira.wide.dgrad.c36.k8", 4, 75, 200, 36, 8, 5, 5, 1, 2, 1), "f16", "dgrad"),         # columns not a multiple of 8
+    (L("tira.wide.fwd.c32.k80", 3, 100, 230, 32, 80, 5, 5, 1, 2, 1), "bf16", "fwd"),         # taps not mirrored
+    (L("tira.wide.fwd.c16.k40.pad3", 2, 120, 250, 16, 40, 5, 5, 1, 3, 1), "f16", "fwd"),
+]
+
+
+@pytest.mark.parametrize("layer,dtype,which", WIDE, ids=[l.name for l, _, _ in WIDE])
+def test_wide_5x5_kernel(api, layer, dtype, which):
+    check_layer(api, layer, dtype, synth.seed_for(6, 170 + [l.name for l, _, _ in WIDE].index(layer.name)), passes=(which,))
+
+
 def test_filter_gradient_5x5_slices_and_edges(api):
     """The 5x5 filter-gradient kernel where its slicing shows: a map whose width is not a multiple of the
     32-pixel strip and whose height does not divide into equal row ranges, 3 images, a partial channel block
