@@ -1,8 +1,10 @@
-// Halo-tile implicit-GEMM kernel for dense 5x5 filters with unit stride and
-// dilation and at most 32 output channels (gfx950): the forward pass of the
-// dense-block layers of a Tiramisu-style network (growth rate 32), where a
-// 256- or 128-wide column tile would be mostly padding and the plain engine
-// re-fetches the activation tile from L2 for each of the 25 taps.
+// Halo-tile implicit-GEMM kernels for dense 5x5 filters with unit stride and
+// dilation where one side of the layer has at most 32 channels (gfx950): the
+// dense-block layers of a Tiramisu-style network (growth rate 32).  First the
+// forward pass (at most 32 OUTPUT channels), where a 256- or 128-wide column
+// tile would be mostly padding and the plain engine re-fetches the activation
+// tile from L2 for each of the 25 taps; further down its mirror image, the
+// data gradient (at most 32 channels on the reduction side).
 //
 // A workgroup (4 waves) owns a 16-row x 32-column patch of output pixels and
 // all output channels; wave w owns patch rows 4w .. 4w+3.  Per 32-channel
