@@ -43,6 +43,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dtype", default="f16", choices=("f16", "bf16"),
                     help="storage type of the tensors (the headline configuration is f16; accumulation is fp32 either way)")
+    ap.add_argument("--activations", default="abs", choices=("abs", "relu"),
+                    help="distribution of the layers' input activations: |N(0,1)| (dense, the headline recipe) or "
+                         "max(N(0,1), 0) (half of them exactly zero, as behind a ReLU at initialisation); the chip is "
+                         "power-limited, so the time depends on the operand values")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
     ap.add_argument("--tiramisu-table", action="store_true",
                     help="per-layer times at the layer shapes of the paper's second network (modified Tiramisu); "
@@ -59,7 +63,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def device_inputs(layer, dtype, seed, torch):
+def device_inputs(layer, dtype, seed, torch, activations="abs"):
     """Synthetic tensors of the layer's shapes, generated on the device:
     |N(0,1)| activations (post-ReLU-like), He-scaled filters, N(0,1) upstream
     gradients; the stem gets smooth normalised fields from the host generator."""
@@ -71,7 +75,8 @@ def device_inputs(layer, dtype, seed, torch):
         _, bits = synth.quantize(synth.smooth_fields(seed, *xs), "bf16" if dtype == torch.bfloat16 else "f16")
         x = torch.from_numpy(bits.view(np.int16)).view(dtype).cuda()
     else:
-        x = torch.randn(xs, generator=g, device="cuda", dtype=torch.float32).abs_().to(dtype)
+        x = torch.randn(xs, generator=g, device="cuda", dtype=torch.float32)
+        x = (x.abs_() if activations == "abs" else x.clamp_(min=0)).to(dtype)
     sigma = float(np.sqrt(2.0 / (layer.R * layer.S * layer.C)))
     w = (torch.randn((layer.K, layer.R, layer.S, layer.C), generator=g, device="cuda") * sigma).to(dtype)
     dy = torch.randn((layer.N, layer.P, layer.Q, layer.K), generator=g, device="cuda", dtype=torch.float32).to(dtype)
@@ -81,10 +86,11 @@ def device_inputs(layer, dtype, seed, torch):
 class LayerState:
     """Device buffers of one occurrence of one layer shape."""
 
-    def __init__(self, api, layer, seed, torch, dtype_name="f16"):
+    def __init__(self, api, layer, seed, torch, dtype_name="f16", activations="abs"):
         self.layer = layer
         self.desc = api.desc_from_layer(layer, dtype_name)
-        self.x, self.w, self.dy = device_inputs(layer, torch.bfloat16 if dtype_name == "bf16" else torch.float16, seed, torch)
+        self.x, self.w, self.dy = device_inputs(layer, torch.bfloat16 if dtype_name == "bf16" else torch.float16, seed, torch,
+                                                 activations)
         self.y = torch.empty_like(self.dy)
         self.dx = torch.empty_like(self.x)
         self.dw = torch.empty_like(self.w)
@@ -285,7 +291,7 @@ def main():
     net = []
     for li, layer in enumerate(table):
         for occ in range(layer.count):
-            net.append(LayerState(api, layer, synth.seed_for(5, 100 * li + occ), torch, args.dtype))
+            net.append(LayerState(api, layer, synth.seed_for(5, 100 * li + occ), torch, args.dtype, args.activations))
     n_pix = 2 * 768 * 1152
     tdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float16
     logits = torch.randn((n_pix, 3), device="cuda").to(tdtype)
@@ -423,7 +429,7 @@ def main():
         "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": f"config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, {'bf16' if args.dtype == 'bf16' else 'fp16'} in / fp32 accumulate",
-                   "streams": args.streams,
+                   "streams": args.streams, "activations": args.activations,
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
                    "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9,
