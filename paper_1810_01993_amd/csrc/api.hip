@@ -189,11 +189,11 @@ bool use_wgrad5x5(const dl_conv_desc *d)
 dlk::WgradPlan wgrad_plan(const dl_conv_desc *d, const Geometry &g)
 {
     if (use_wgrad5x5(d)) {
-        const dlk::Wgrad3x3Plan p5 = dlk::wgrad5x5_make_plan(d->N, d->H, d->W, d->C, d->K);
+        const dlk::WgradStripPlan p5 = dlk::wgrad5x5_make_plan(d->N, d->H, d->W, d->C, d->K);
         return dlk::WgradPlan{-4, p5.slices, 0};
     }
     if (use_wgrad3x3(d)) {
-        const dlk::Wgrad3x3Plan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
+        const dlk::WgradStripPlan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
         return dlk::WgradPlan{-3, p3.slices, 0};
     }
     const bool thin = dlk::thin_wgrad_applicable(d->K, d->C, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w);
@@ -410,15 +410,15 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     a.spread = plan.spread;
     hipError_t e;
     if (plan.cfg == -3) {
-        const dlk::Wgrad3x3Plan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
-        dlk::Wgrad3x3Args w{};
+        const dlk::WgradStripPlan p3 = dlk::wgrad3x3_make_plan(d->N, d->H, d->W, d->C, d->K);
+        dlk::WgradStripArgs w{};
         w.x = a.x; w.dy = a.dy; w.partial = a.partial;
         w.N = d->N; w.H = d->H; w.W = d->W; w.C = d->C; w.K = d->K;
         w.slices = p3.slices; w.rs = p3.rs; w.xs = p3.xs;
         e = dlk::launch_wgrad3x3(w, d->dtype == DL_BF16, stream);
     } else if (plan.cfg == -4) {
-        const dlk::Wgrad3x3Plan p5 = dlk::wgrad5x5_make_plan(d->N, d->H, d->W, d->C, d->K);
-        dlk::Wgrad3x3Args w{};
+        const dlk::WgradStripPlan p5 = dlk::wgrad5x5_make_plan(d->N, d->H, d->W, d->C, d->K);
+        dlk::WgradStripArgs w{};
         w.x = a.x; w.dy = a.dy; w.partial = a.partial;
         w.N = d->N; w.H = d->H; w.W = d->W; w.C = d->C; w.K = d->K;
         w.slices = p5.slices; w.rs = p5.rs; w.xs = p5.xs;

@@ -150,25 +150,25 @@ struct WgradPlan {
 };
 WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok);
 
-// Filter gradient of dense 3x3, stride 1, dilation 1, padding 1 layers on large images
-// (cfg -3 of the plan): all nine taps per workgroup, partial[slice][K][9][C].
-struct Wgrad3x3Args {
+// Filter gradient of dense RxR (3x3 or 5x5), stride 1, dilation 1, "same"-padded layers on large images by
+// the strip-walk kernels (cfg -3 / -4 of the plan): all taps per workgroup, partial[slice][K][R*R][C].
+struct WgradStripArgs {
     const uint16_t *x;          // [N,H,W,C]
     const uint16_t *dy;         // [N,H,W,K]
-    float *partial;             // [slices][K][3][3][C]
+    float *partial;             // [slices][K][R][R][C]
     int32_t N, H, W, C, K;
     int32_t slices;             // N * ceil(H / rs) * ceil(ceil(W / 32) / xs)
     int32_t rs, xs;             // image rows and 32-pixel strips per slice
 };
-struct Wgrad3x3Plan { int slices, rs, xs; };
+struct WgradStripPlan { int slices, rs, xs; };
 bool wgrad3x3_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw);
-Wgrad3x3Plan wgrad3x3_make_plan(int N, int H, int W, int C, int K);
-hipError_t launch_wgrad3x3(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream);
+WgradStripPlan wgrad3x3_make_plan(int N, int H, int W, int C, int K);
+hipError_t launch_wgrad3x3(const WgradStripArgs &a, bool is_bf16, hipStream_t stream);
 // The same for dense 5x5, stride 1, padding 2 with at most 32 output channels (same argument and plan structs;
 // partial sums [slice][K][5][5][C]).
 bool wgrad5x5_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw);
-Wgrad3x3Plan wgrad5x5_make_plan(int N, int H, int W, int C, int K);
-hipError_t launch_wgrad5x5(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream);
+WgradStripPlan wgrad5x5_make_plan(int N, int H, int W, int C, int K);
+hipError_t launch_wgrad5x5(const WgradStripArgs &a, bool is_bf16, hipStream_t stream);
 
 // Streaming kernels for 1x1 layers with <= 4 channels on one side (cfg -2 of the plan).
 bool thin_rows_applicable(const IgemmArgs &a);

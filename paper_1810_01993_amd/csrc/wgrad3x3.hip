@@ -41,7 +41,7 @@ namespace dlk {
 typedef short w3_s16x4_t __attribute__((ext_vector_type(4)));
 
 template <class T>
-__global__ __launch_bounds__(512) void wgrad3x3_kernel(const Wgrad3x3Args p)
+__global__ __launch_bounds__(512) void wgrad3x3_kernel(const WgradStripArgs p)
 {
     constexpr int NW = 8;
     constexpr int KB = 256, CB = 32, PXB = 32;           // k per workgroup, c per workgroup, strip width
@@ -248,12 +248,12 @@ bool wgrad3x3_applicable(int N, int H, int W, int C, int K, int R, int S, int sh
 // Rows and strips per slice: what counts is how many rounds of workgroups the busiest XCD
 // (32 CUs, one workgroup each) runs and how long a workgroup's run of steps is, plus the
 // fp32 partial sums written and read back once per slice.
-Wgrad3x3Plan wgrad3x3_make_plan(int N, int H, int W, int C, int K)
+WgradStripPlan wgrad3x3_make_plan(int N, int H, int W, int C, int K)
 {
     const int tiles = ((C + 31) / 32) * ((K + 255) / 256);
     const int xblocks = (W + 31) / 32;
     const double outputs = (double)K * 9 * C;
-    Wgrad3x3Plan best{0, 0, 0};
+    WgradStripPlan best{0, 0, 0};
     double best_cost = 1e300;
     for (int nrs = 1; nrs <= H / 8 && nrs <= 64; ++nrs) {
         const int rs = (H + nrs - 1) / nrs;
@@ -269,14 +269,14 @@ Wgrad3x3Plan wgrad3x3_make_plan(int N, int H, int W, int C, int K)
             const double cost = rounds * steps * 0.55 + slices * outputs * 8.0 / 11.5e6;
             if (cost < best_cost) {
                 best_cost = cost;
-                best = Wgrad3x3Plan{(int)slices, rs, xs};
+                best = WgradStripPlan{(int)slices, rs, xs};
             }
         }
     }
     return best;
 }
 
-hipError_t launch_wgrad3x3(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream)
+hipError_t launch_wgrad3x3(const WgradStripArgs &a, bool is_bf16, hipStream_t stream)
 {
     const int64_t tiles = (int64_t)((a.C + 31) / 32) * ((a.K + 255) / 256);
     const int64_t blocks = tiles * ((a.slices + 7) / 8) * 8;

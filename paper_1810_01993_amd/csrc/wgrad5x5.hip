@@ -40,7 +40,7 @@ namespace dlk {
 typedef short w5_s16x4_t __attribute__((ext_vector_type(4)));
 
 template <class T>
-__global__ __launch_bounds__(320) void wgrad5x5_kernel(const Wgrad3x3Args p)
+__global__ __launch_bounds__(320) void wgrad5x5_kernel(const WgradStripArgs p)
 {
     constexpr int NTAP = 5, PAD = 2;                     // five waves: one per column shift
     constexpr int KBLK = 32, CB = 32, PXB = 32;          // k per workgroup (all of them), c per workgroup, strip width
@@ -209,12 +209,12 @@ bool wgrad5x5_applicable(int N, int H, int W, int C, int K, int R, int S, int sh
 
 // Rows and strips per slice: rounds of workgroups on the busiest XCD (32 CUs, two workgroups each),
 // the length of a workgroup's run of steps, and the fp32 partial sums written and read back once per slice.
-Wgrad3x3Plan wgrad5x5_make_plan(int N, int H, int W, int C, int K)
+WgradStripPlan wgrad5x5_make_plan(int N, int H, int W, int C, int K)
 {
     const int tiles = (C + 31) / 32;
     const int xblocks = (W + 31) / 32;
     const double outputs = (double)K * 25 * C;
-    Wgrad3x3Plan best{0, 0, 0};
+    WgradStripPlan best{0, 0, 0};
     double best_cost = 1e300;
     for (int nrs = 1; nrs <= H / 8 && nrs <= 64; ++nrs) {
         const int rs = (H + nrs - 1) / nrs;
@@ -230,14 +230,14 @@ Wgrad3x3Plan wgrad5x5_make_plan(int N, int H, int W, int C, int K)
             const double cost = rounds * steps * 0.35 + slices * outputs * 8.0 / 4.0e6;
             if (cost < best_cost) {
                 best_cost = cost;
-                best = Wgrad3x3Plan{(int)slices, rs, xs};
+                best = WgradStripPlan{(int)slices, rs, xs};
             }
         }
     }
     return best;
 }
 
-hipError_t launch_wgrad5x5(const Wgrad3x3Args &a, bool is_bf16, hipStream_t stream)
+hipError_t launch_wgrad5x5(const WgradStripArgs &a, bool is_bf16, hipStream_t stream)
 {
     const int64_t tiles = (a.C + 31) / 32;
     const int64_t blocks = tiles * ((a.slices + 7) / 8) * 8;
