@@ -204,6 +204,31 @@ dl_status weighted_pixel_ce_map_fwd_bwd(const void *logits, int32_t dtype, const
                                         float *loss, void *dlogits,
                                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The logits layer fused with the loss (the paper's stated next optimisation,
+ * Sec. "Single GPU performance": fuse point-wise work into neighbouring layers
+ * so that tensors cross DRAM fewer times; the loss of Sec. "Weighted loss"):
+ * the 1x1 convolution from C channels to the 3 classes, the class-weighted
+ * softmax cross-entropy and both gradients of that convolution in one pass
+ * over x,
+ *   z_i = W x_i;   loss = scale * sum_i class_weights[label_i] * (-log softmax(z_i)[label_i])
+ *   dz_i = scale * class_weights[label_i] * (softmax(z_i) - onehot(label_i))
+ *   dx_i = W^T dz_i;   dW = sum_i dz_i x_i^T
+ * x, dx: [n_pixels, C] in `dtype` (F16 | BF16), C % 8 == 0, 32 <= C <= 2048;
+ * w: [3, C] in `dtype` (a [3,1,1,C] filter); labels, class_weights, loss as for
+ * weighted_pixel_ce_fwd_bwd; logits, dlogits: [n_pixels, 3] in `dtype`, each
+ * optional (null: not written; they are copies rounded on store: the loss and
+ * the gradients are formed from the unrounded fp32 values); dw: [3, C] in
+ * dw_dtype (`dtype` or F32).  All device memory, caller-owned, 16-byte aligned
+ * bases; outputs are overwritten.  Sums over pixels are added in a fixed order
+ * (run-to-run identical).  Traffic: 4*C + 1 bytes per pixel against 6*C + 13
+ * for the four separate calls.  Workspace: dl_logits_ce_workspace_bytes.
+ * Errors as for the other entry points, before any launch. */
+dl_status dl_logits_ce_workspace_bytes(int64_t n_pixels, int32_t C, size_t *bytes);
+dl_status logits_ce_fused_fwd_bwd(const void *x, const void *w, int32_t dtype, const uint8_t *labels,
+                                  const float *class_weights, float scale, int64_t n_pixels, int32_t C, void *logits,
+                                  float *loss, void *dlogits, void *dx, void *dw, int32_t dw_dtype, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream);
+
 const char *dl_status_string(dl_status s);
 
 #ifdef __cplusplus

@@ -21,7 +21,8 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
-           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd", "dl_status_string")
+           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd",
+           "dl_logits_ce_workspace_bytes", "logits_ce_fused_fwd_bwd", "dl_status_string")
 
 
 class DlError(RuntimeError):
@@ -82,6 +83,9 @@ def _load() -> ctypes.CDLL:
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
     for name in ("weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd"):
         getattr(lib, name).argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp, sz, vp]
+    lib.dl_logits_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.logits_ce_fused_fwd_bwd.argtypes = [vp, vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, ctypes.c_int32,
+                                            vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     lib.dl_status_string.argtypes = [ctypes.c_int]
@@ -370,6 +374,36 @@ def weighted_pixel_ce_map_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, we
                                               _dev_ptr(dlogits), _dev_ptr(ws), nb, _stream()),
            "weighted_pixel_ce_map_fwd_bwd")
     return loss, dlogits
+
+
+def logits_ce_fused_fwd_bwd(x: torch.Tensor, w: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,
+                            scale: float, want_logits: bool = True, want_dlogits: bool = True, dw_f32: bool = False,
+                            dx: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """The logits layer (1x1 convolution to the 3 classes) fused with the weighted loss: x [..., C]
+    fp16/bf16, w [3, C] (or [3,1,1,C]) of the same type, labels [...] uint8, class_weights float32[3].
+    Returns (logits or None, loss: float32[1] device tensor, dlogits or None, dx, dw)."""
+    C = x.shape[-1]
+    n = labels.numel()
+    if x.numel() != n * C or w.numel() != 3 * C or w.dtype != x.dtype or labels.dtype != torch.uint8:
+        raise ValueError("x [..., C], w [3, C] of one dtype and uint8 labels with one entry per pixel expected")
+    if class_weights.dtype != torch.float32 or class_weights.numel() != 3:
+        raise ValueError("class_weights must be float32[3]")
+    dev = x.device
+    logits = torch.empty((n, 3), dtype=x.dtype, device=dev) if want_logits else None
+    dlogits = torch.empty((n, 3), dtype=x.dtype, device=dev) if want_dlogits else None
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    if dx is None:
+        dx = torch.empty_like(x)
+    dw = torch.empty(w.shape, dtype=torch.float32 if dw_f32 else w.dtype, device=dev)
+    need = ctypes.c_size_t(0)
+    _check(_lib.dl_logits_ce_workspace_bytes(n, C, ctypes.byref(need)), "dl_logits_ce_workspace_bytes")
+    ws, nb = _workspace(int(need.value), dev, workspace)
+    _check(_lib.logits_ce_fused_fwd_bwd(_dev_ptr(x), _dev_ptr(w), _dtype_code(x), _dev_ptr(labels), _dev_ptr(class_weights),
+                                        ctypes.c_float(scale), n, C, _dev_ptr(logits) if want_logits else None,
+                                        _dev_ptr(loss), _dev_ptr(dlogits) if want_dlogits else None, _dev_ptr(dx),
+                                        _dev_ptr(dw), DL_F32 if dw_f32 else _dtype_code(x), _dev_ptr(ws), nb, _stream()),
+           "logits_ce_fused_fwd_bwd")
+    return logits, loss, dlogits, dx, dw
 
 
 def desc_from_layer(layer, dtype: str, dw_f32: bool = False) -> ConvDesc:

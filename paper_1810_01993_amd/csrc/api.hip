@@ -211,6 +211,49 @@ dl_status hip_status(hipError_t e) { return e == hipSuccess ? DL_OK : DL_ERR_LAU
 
 extern "C" {
 
+dl_status dl_logits_ce_workspace_bytes(int64_t n_pixels, int32_t C, size_t *bytes)
+{
+    if (!bytes) return DL_ERR_NULL;
+    if (n_pixels < 0 || C < 32 || C > 2048 || C % 8 != 0) return DL_ERR_SHAPE;
+    const size_t blocks = (size_t)dlk::logits_ce_blocks(n_pixels, C);
+    *bytes = align_up(blocks * 3 * (size_t)C * sizeof(float), 256) + align_up(blocks * sizeof(float), 256);
+    return DL_OK;
+}
+
+dl_status logits_ce_fused_fwd_bwd(const void *x, const void *w, int32_t dtype, const uint8_t *labels,
+                                  const float *class_weights, float scale, int64_t n_pixels, int32_t C, void *logits,
+                                  float *loss, void *dlogits, void *dx, void *dw, int32_t dw_dtype, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
+{
+    if (!w || !class_weights || !loss || !dw) return DL_ERR_NULL;
+    if (n_pixels < 0 || C < 32 || C > 2048 || C % 8 != 0 || n_pixels >= MAX_ELEMS / C) return DL_ERR_SHAPE;
+    if (n_pixels > 0 && (!x || !labels || !dx)) return DL_ERR_NULL;
+    if ((dtype != DL_F16 && dtype != DL_BF16) || (dw_dtype != dtype && dw_dtype != DL_F32)) return DL_ERR_DTYPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(dx) || !aligned16(dw)) return DL_ERR_ALIGN;
+    size_t need = 0;
+    dl_logits_ce_workspace_bytes(n_pixels, C, &need);
+    if (!workspace || workspace_bytes < need) return DL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DL_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int blocks = dlk::logits_ce_blocks(n_pixels, C);
+    dlk::LogitsCeArgs a{};
+    a.x = static_cast<const uint16_t *>(x);
+    a.w = static_cast<const uint16_t *>(w);
+    a.labels = labels;
+    a.cw = class_weights;
+    a.scale = scale;
+    a.n = n_pixels;
+    a.C = C;
+    a.logits = static_cast<uint16_t *>(logits);
+    a.dlogits = static_cast<uint16_t *>(dlogits);
+    a.dx = static_cast<uint16_t *>(dx);
+    a.partial_dw = static_cast<float *>(workspace);
+    a.partial_loss = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)blocks * 3 * C * sizeof(float), 256));
+    if (dlk::launch_logits_ce(a, dtype == DL_BF16, stream) != hipSuccess) return DL_ERR_LAUNCH;
+    if (dlk::launch_splitk_reduce(a.partial_dw, blocks, (int64_t)3 * C, dw, dw_dtype, stream) != hipSuccess) return DL_ERR_LAUNCH;
+    return hip_status(dlk::launch_ce_finish(a.partial_loss, blocks, scale, loss, stream));
+}
+
 const char *dl_status_string(dl_status s)
 {
     switch (s) {

@@ -209,6 +209,25 @@ hipError_t launch_larc(const LarcBatch &b, int grad_dtype, hipStream_t stream);
 
 // Weighted per-pixel cross-entropy, 3 classes.
 int ce_num_blocks(int64_t n_pixels);
+// The logits layer (1x1, C -> 3) fused with the loss: one pass over x.  C % 8 == 0, 32 <= C <= 2048.
+struct LogitsCeArgs {
+    const uint16_t *x;          // [n][C]
+    const uint16_t *w;          // [3][C]
+    const uint8_t *labels;      // [n]
+    const float *cw;            // [3]
+    float scale;
+    int64_t n;
+    int32_t C;
+    uint16_t *logits;           // [n][3] or null
+    uint16_t *dlogits;          // [n][3] or null
+    uint16_t *dx;               // [n][C]
+    float *partial_dw;          // [blocks][3][C]
+    float *partial_loss;        // [blocks]
+};
+int logits_ce_blocks(int64_t n_pixels, int C);
+hipError_t launch_logits_ce(const LogitsCeArgs &a, bool is_bf16, hipStream_t stream);
+// loss[0] = scale * (sum of the partials, in a fixed order)
+hipError_t launch_ce_finish(const float *partials, int n_partials, float scale, float *loss, hipStream_t stream);
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
                               bool per_pixel, float scale, int64_t n_pixels, float *loss, uint16_t *dlogits,
                               float *partials, hipStream_t stream);

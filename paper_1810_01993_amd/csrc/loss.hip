@@ -193,6 +193,12 @@ __global__ __launch_bounds__(CE_THREADS) void ce_finish_kernel(const float *__re
     if (threadIdx.x == 0) loss[0] = scale * ((wsum[0] + wsum[1]) + (wsum[2] + wsum[3]));
 }
 
+hipError_t launch_ce_finish(const float *partials, int n_partials, float scale, float *loss, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, n_partials, scale, loss);
+    return hipGetLastError();
+}
+
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
                               bool per_pixel, float scale, int64_t n_pixels, float *loss, uint16_t *dlogits,
                               float *partials, hipStream_t stream)
