@@ -47,6 +47,9 @@ def parse_args():
                     help="distribution of the layers' input activations: |N(0,1)| (dense, the headline recipe) or "
                          "max(N(0,1), 0) (half of them exactly zero, as behind a ReLU at initialisation); the chip is "
                          "power-limited, so the time depends on the operand values")
+    ap.add_argument("--fused-logits", action="store_true",
+                    help="run the logits layer and the loss as the one fused call (logits_ce_fused_fwd_bwd) instead of "
+                         "forward + loss + data gradient + filter gradient; not the headline configuration")
     ap.add_argument("--table", action="store_true", help="per-layer timing table on stderr")
     ap.add_argument("--tiramisu-table", action="store_true",
                     help="per-layer times at the layer shapes of the paper's second network (modified Tiramisu); "
@@ -308,6 +311,10 @@ def main():
     timed.add(("loss", "loss"))
 
     side_streams = [torch.cuda.Stream() for _ in range(args.streams - 1)]   # default priority
+    fused_i, fused_ws = None, None
+    if args.fused_logits:
+        fused_i = next(i for i, st in enumerate(net) if st.layer.name.startswith("logits"))
+        fused_ws = torch.empty(api.logits_ce_workspace_bytes(n_pix, net[fused_i].layer.C), dtype=torch.uint8, device="cuda")
 
     def step(events=None):
         def rec(key):
@@ -316,11 +323,18 @@ def main():
                 e.record()
                 events.append((key, e))
         for i, st in enumerate(net):
+            if i == fused_i:
+                continue
             rec((i, "fwd", 0))
             api.conv2d_fwd(st.desc, st.x, st.w, y=st.y, workspace=st.ws)
             rec((i, "fwd", 1))
         rec(("loss", "loss", 0))
-        api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n_pix, loss=loss, dlogits=dlogits, workspace=ce_ws)
+        if fused_i is None:
+            api.weighted_pixel_ce_fwd_bwd(logits, labels, cw, 1.0 / n_pix, loss=loss, dlogits=dlogits, workspace=ce_ws)
+        else:       # forward, loss and both gradients of the logits layer: one pass over its input
+            st = net[fused_i]
+            api.logits_ce_fused_fwd_bwd(st.x.view(n_pix, -1), st.w, labels, cw, 1.0 / n_pix, dx=st.dx.view(n_pix, -1),
+                                        workspace=fused_ws, logits=st.y.view(n_pix, 3), dlogits=dlogits, loss=loss, dw=st.dw)
         rec(("loss", "loss", 1))
         # Backward.  In the network, layer i's filter gradient and data gradient both consume
         # dy_i, which the layer above has produced before either starts.  With several streams the
@@ -330,6 +344,8 @@ def main():
         # its dy exists; the large decoder layers and the bandwidth-bound full-resolution logits
         # layer, which fill the chip by themselves, keep both passes on the main stream.
         for i in range(len(net) - 1, -1, -1):
+            if i == fused_i:
+                continue
             st = net[i]
             side = bool(side_streams) and st.layer.flops() < 1e12 and st.layer.bytes_fwd() < 2e8
             if side:
@@ -406,6 +422,8 @@ def main():
               file=sys.stderr)
         for i, st in enumerate(net):
             for which in ("fwd", "dgrad", "wgrad"):
+                if (i, which) not in med:                 # --fused-logits: inside the "loss" line
+                    continue
                 ms = med[(i, which)]
                 tf = st.layer.flops() / (ms * 1e-3) / 1e12
                 gbs = st.layer.bytes_fwd() / (ms * 1e-3) / 1e9
@@ -429,7 +447,7 @@ def main():
         "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": f"config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, {'bf16' if args.dtype == 'bf16' else 'fp16'} in / fp32 accumulate",
-                   "streams": args.streams, "activations": args.activations,
+                   "streams": args.streams, "activations": args.activations, "fused_logits": bool(args.fused_logits),
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
                    "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9,

@@ -378,7 +378,9 @@ def weighted_pixel_ce_map_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, we
 
 def logits_ce_fused_fwd_bwd(x: torch.Tensor, w: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,
                             scale: float, want_logits: bool = True, want_dlogits: bool = True, dw_f32: bool = False,
-                            dx: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+                            dx: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                            logits: torch.Tensor | None = None, dlogits: torch.Tensor | None = None,
+                            loss: torch.Tensor | None = None, dw: torch.Tensor | None = None):
     """The logits layer (1x1 convolution to the 3 classes) fused with the weighted loss: x [..., C]
     fp16/bf16, w [3, C] (or [3,1,1,C]) of the same type, labels [...] uint8, class_weights float32[3].
     Returns (logits or None, loss: float32[1] device tensor, dlogits or None, dx, dw)."""
@@ -389,12 +391,22 @@ def logits_ce_fused_fwd_bwd(x: torch.Tensor, w: torch.Tensor, labels: torch.Tens
     if class_weights.dtype != torch.float32 or class_weights.numel() != 3:
         raise ValueError("class_weights must be float32[3]")
     dev = x.device
-    logits = torch.empty((n, 3), dtype=x.dtype, device=dev) if want_logits else None
-    dlogits = torch.empty((n, 3), dtype=x.dtype, device=dev) if want_dlogits else None
-    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    if want_logits and logits is None:
+        logits = torch.empty((n, 3), dtype=x.dtype, device=dev)
+    if want_dlogits and dlogits is None:
+        dlogits = torch.empty((n, 3), dtype=x.dtype, device=dev)
+    for t in (logits if want_logits else None, dlogits if want_dlogits else None):
+        if t is not None and (t.dtype != x.dtype or t.numel() != 3 * n):
+            raise ValueError("logits / dlogits must be [n, 3] of x's dtype")
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
     if dx is None:
         dx = torch.empty_like(x)
-    dw = torch.empty(w.shape, dtype=torch.float32 if dw_f32 else w.dtype, device=dev)
+    if dw is None:
+        dw = torch.empty(w.shape, dtype=torch.float32 if dw_f32 else w.dtype, device=dev)
+    if dx.dtype != x.dtype or dx.numel() != x.numel() or dw.numel() != w.numel() or \
+            dw.dtype != (torch.float32 if dw_f32 else w.dtype) or loss.dtype != torch.float32:
+        raise ValueError("dx must match x, dw must match w (or float32 with dw_f32), loss must be float32[1]")
     need = ctypes.c_size_t(0)
     _check(_lib.dl_logits_ce_workspace_bytes(n, C, ctypes.byref(need)), "dl_logits_ce_workspace_bytes")
     ws, nb = _workspace(int(need.value), dev, workspace)
@@ -403,7 +415,13 @@ def logits_ce_fused_fwd_bwd(x: torch.Tensor, w: torch.Tensor, labels: torch.Tens
                                         _dev_ptr(loss), _dev_ptr(dlogits) if want_dlogits else None, _dev_ptr(dx),
                                         _dev_ptr(dw), DL_F32 if dw_f32 else _dtype_code(x), _dev_ptr(ws), nb, _stream()),
            "logits_ce_fused_fwd_bwd")
-    return logits, loss, dlogits, dx, dw
+    return (logits if want_logits else None), loss, (dlogits if want_dlogits else None), dx, dw
+
+
+def logits_ce_workspace_bytes(n_pixels: int, C: int) -> int:
+    need = ctypes.c_size_t(0)
+    _check(_lib.dl_logits_ce_workspace_bytes(n_pixels, C, ctypes.byref(need)), "dl_logits_ce_workspace_bytes")
+    return int(need.value)
 
 
 def desc_from_layer(layer, dtype: str, dw_f32: bool = False) -> ConvDesc:
