@@ -9,7 +9,10 @@ and written fewer times, as the optimisation being pursued (Sec. "Single GPU
 Performance").  The definition is the convolution of ``oracle.c`` followed by
   y[n,p,q,k] <- y[n,p,q,k] + bias[k]            (bias: one value per output channel)
   y          <- max(y, 0)                        (if relu)
-applied to the un-rounded fp64 sums.
+applied to the un-rounded fp64 sums.  With a residual input (the skip
+connection of a ResNet block, which is added to the block's last convolution
+before the activation) the middle line is
+  y[n,p,q,k] <- y[n,p,q,k] + bias[k] + residual[n,p,q,k].
 """
 from __future__ import annotations
 
@@ -25,6 +28,30 @@ def conv_fwd_bias_relu(s: ConvShape, x, w, bias=None, relu: bool = False) -> np.
         if b.shape != (s.K,):
             raise ValueError("bias must have one entry per output channel")
         y = y + b[None, None, None, :]
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
+
+
+def conv_fwd_bias_add_relu(s: ConvShape, x, w, bias=None, residual=None, relu: bool = False) -> np.ndarray:
+    """act(conv(x, w) + bias + residual); residual has the shape of the output."""
+    y = conv_fwd_bias_relu(s, x, w, bias, False)
+    if residual is not None:
+        r = np.asarray(residual, dtype=np.float64)
+        if r.shape != y.shape:
+            raise ValueError("the residual must have the shape of the output")
+        y = y + r
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
+
+
+def conv_fwd_bias_add_relu_at(s: ConvShape, x32, w32, bias, residual32, relu: bool, flat_idx) -> np.ndarray:
+    """Single output elements (float32 storage, double arithmetic)."""
+    idx = np.asarray(flat_idx, dtype=np.int64)
+    y = conv_fwd_bias_relu_at(s, x32, w32, bias, False, idx)
+    if residual32 is not None:
+        y = y + np.asarray(residual32).ravel()[idx].astype(np.float64)
     if relu:
         y = np.maximum(y, 0.0)
     return y

@@ -75,3 +75,30 @@ def test_tail_backward_against_autograd(oracle):
     # dz is what the convolution's own gradients take: chain it through the oracle's data and filter gradients
     assert np.allclose(oracle.conv_bwd_data(s, dz, w), xt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
     assert np.allclose(oracle.conv_bwd_filter(s, x, dz), wt.grad.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
+
+
+def test_residual_hand_example_and_library():
+    # the hand example above with a residual of (1, -3, -20): sums (-0.5, 1, 6) + r = (0.5, -2, -14)
+    s = ConvShape(1, 1, 1, 2, 3, 1, 1)
+    x = np.array([1.0, -2.0]).reshape(1, 1, 1, 2)
+    w = np.array([[1.0, 1.0], [3.0, 0.5], [0.0, 2.0]]).reshape(3, 1, 1, 2)
+    b = np.array([0.5, -1.0, 10.0])
+    r = np.array([1.0, -3.0, -20.0]).reshape(1, 1, 1, 3)
+    assert np.array_equal(E.conv_fwd_bias_add_relu(s, x, w, b, r, False).ravel(), [0.5, -2.0, -14.0])
+    assert np.array_equal(E.conv_fwd_bias_add_relu(s, x, w, b, r, True).ravel(), [0.5, 0.0, 0.0])
+    assert np.array_equal(E.conv_fwd_bias_add_relu(s, x, w, None, r, True).ravel(), [0.0, 0.0, 0.0])    # (-1, 2, -4) + r
+    # a ResNet block's tail against torch: relu(conv(x) + b + skip), float64
+    s = ConvShape(2, 9, 11, 8, 12, 1, 1, 1, 0, 1)
+    x, w, b = _rand(11, s.N, s.H, s.W, s.C), _rand(12, s.K, 1, 1, s.C), _rand(13, s.K)
+    skip = _rand(14, s.N, s.H, s.W, s.K)
+    y = E.conv_fwd_bias_add_relu(s, x, w, b, skip, True)
+    yt = F.relu(F.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(w).permute(0, 3, 1, 2),
+                         bias=torch.from_numpy(b)) + torch.from_numpy(skip).permute(0, 3, 1, 2))
+    assert np.allclose(y, yt.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-12)
+    # no residual: the plain fused tail; a huge negative residual cuts everything; single elements agree
+    assert np.array_equal(E.conv_fwd_bias_add_relu(s, x, w, b, None, True), E.conv_fwd_bias_relu(s, x, w, b, True))
+    assert not E.conv_fwd_bias_add_relu(s, x, w, b, -1e9 * np.ones_like(skip), True).any()
+    idx = np.random.default_rng(15).integers(0, y.size, 200)
+    x32, w32, r32 = x.astype(np.float32), w.astype(np.float32), skip.astype(np.float32)
+    ref = E.conv_fwd_bias_add_relu(s, x32.astype(np.float64), w32.astype(np.float64), b, r32.astype(np.float64), True).ravel()[idx]
+    assert np.allclose(E.conv_fwd_bias_add_relu_at(s, x32, w32, b, r32, True, idx), ref, rtol=0, atol=1e-13)
