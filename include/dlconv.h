@@ -87,6 +87,19 @@ dl_status conv2d_fwd(const dl_conv_desc *desc, const void *x, const void *w, voi
 dl_status conv2d_fwd_bias_relu(const dl_conv_desc *desc, const void *x, const void *w, const float *bias,
                                int32_t relu, void *y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same with a residual input added before the activation (the tail of a
+ * ResNet block: the skip connection joins the block's last convolution):
+ *   y = act(conv(x, w) + bias[k] + residual)
+ * residual: [N,P,Q,K] in the descriptor's dtype, 16-byte aligned, or null
+ * (then this is conv2d_fwd_bias_relu).  The sum is formed in fp32 and rounded
+ * once.  With a residual the launch takes the kernels that can reach the
+ * residual before rounding (the 3x3 halo-tile kernel and the two 5x5 kernels,
+ * which store through an LDS staging area, are not among them); workspace as
+ * reported by dl_conv_workspace_bytes for the forward pass. */
+dl_status conv2d_fwd_bias_add_relu(const dl_conv_desc *d, const void *x, const void *w, const float *bias,
+                                   const void *residual, int32_t relu, void *y, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
 /* Data gradient (paper, Sec. "Deep learning ...": each layer is
  * differentiable; backward convolutions in the kernel breakdown): the adjoint
  * of conv2d_fwd with respect to x applied to dy.

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libdlconv.so")
 DL_F16, DL_BF16, DL_F32 = 0, 1, 2
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
-EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_bwd_data",
+EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_fwd_bias_add_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
            "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd",
            "dl_logits_ce_workspace_bytes", "logits_ce_fused_fwd_bwd", "dl_status_string")
@@ -75,6 +75,7 @@ def _load() -> ctypes.CDLL:
                  "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter"):
         getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
     lib.conv2d_fwd_bias_relu.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+    lib.conv2d_fwd_bias_add_relu.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
     lib.dl_bias_relu_bwd_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.bias_relu_bwd.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, sz, vp]
     lib.dl_larc_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(sz)]
@@ -183,6 +184,31 @@ def conv2d_fwd_bias_relu(desc: ConvDesc, x: torch.Tensor, w: torch.Tensor, bias:
     _check(_lib.conv2d_fwd_bias_relu(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(w), _dev_ptr(bias),
                                      1 if relu else 0, _dev_ptr(y), _dev_ptr(ws), nb, _stream()),
            "conv2d_fwd_bias_relu")
+    return y
+
+
+def conv2d_fwd_bias_add_relu(desc: ConvDesc, x: torch.Tensor, w: torch.Tensor, bias: torch.Tensor | None,
+                             residual: torch.Tensor | None, relu: bool, y: torch.Tensor | None = None,
+                             workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """y = act(conv(x, w) + bias + residual): residual [N,P,Q,K] of x's dtype or None (a ResNet block's tail)."""
+    P, Q = dl_conv_out_shape(desc)
+    _expect(x, (desc.N, desc.H, desc.W, desc.C), "x")
+    _expect(w, (desc.K, desc.R, desc.S, desc.C), "w")
+    if _dtype_code(x) != desc.dtype or w.dtype != x.dtype:
+        raise TypeError("tensor dtype does not match the descriptor")
+    if bias is not None and (bias.dtype != torch.float32 or tuple(bias.shape) != (desc.K,)):
+        raise ValueError("bias must be float32[K]")
+    if residual is not None:
+        _expect(residual, (desc.N, P, Q, desc.K), "residual")
+        if residual.dtype != x.dtype:
+            raise TypeError("the residual must have x's dtype")
+    if y is None:
+        y = torch.empty((desc.N, P, Q, desc.K), dtype=x.dtype, device=x.device)
+    _expect(y, (desc.N, P, Q, desc.K), "y")
+    ws, nb = _workspace(dl_conv_workspace_bytes(desc, PASS_FWD), x.device, workspace)
+    _check(_lib.conv2d_fwd_bias_add_relu(ctypes.byref(desc.c_struct()), _dev_ptr(x), _dev_ptr(w), _dev_ptr(bias),
+                                         _dev_ptr(residual), 1 if relu else 0, _dev_ptr(y), _dev_ptr(ws), nb, _stream()),
+           "conv2d_fwd_bias_add_relu")
     return y
 
 

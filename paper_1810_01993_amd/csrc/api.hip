@@ -1,6 +1,7 @@
 // C boundary: argument validation, workspace sizing, and the mapping of the
 // three convolution passes and the loss onto the gfx950 kernels.  Everything
 // here runs on the host; validation happens before any launch.
+#include <algorithm>
 #include <hip/hip_runtime.h>
 
 #include "../../include/dlconv.h"
@@ -111,6 +112,7 @@ hipError_t run_igemm(const dlk::IgemmArgs &a, bool bf16, const FilterSrc &fs, ui
     r.B = a.B + (size_t)cols * a.TR * a.TS * a.Cin;
     r.D = a.D + cols;
     if (a.bias) r.bias = a.bias + cols;
+    if (a.resid) r.resid = a.resid + cols;
     return dlk::launch_igemm(r, bf16, stream);
 }
 
@@ -287,7 +289,14 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
     const dl_status st = check_desc(desc, &g);
     if (st != DL_OK) return st;
     switch (pass) {
-        case DL_PASS_FWD: *bytes = igemm_scratch_bytes(fwd_args(desc, g)); return DL_OK;
+        case DL_PASS_FWD: {
+            // with a residual input some kernels are not available and the choice of scratch changes: enough for either
+            dlk::IgemmArgs a = fwd_args(desc, g);
+            const size_t plain = igemm_scratch_bytes(a);
+            a.resid = reinterpret_cast<const uint16_t *>(a.resid) + 8;      // any non-null value: only tested for null
+            *bytes = std::max(plain, igemm_scratch_bytes(a));
+            return DL_OK;
+        }
         case DL_PASS_BWD_DATA: *bytes = dgrad_workspace(desc, g); return DL_OK;
         case DL_PASS_BWD_FILTER: *bytes = wgrad_workspace(desc, g); return DL_OK;
     }
@@ -295,16 +304,18 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
 }
 
 namespace {
-dl_status run_fwd(const dl_conv_desc *d, const void *x, const void *w, const float *bias, int relu, void *y,
-                  void *workspace, size_t workspace_bytes, void *hip_stream)
+dl_status run_fwd(const dl_conv_desc *d, const void *x, const void *w, const float *bias, const void *residual, int relu,
+                  void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!d || !x || !w || !y) return DL_ERR_NULL;
+    if (residual && !aligned16(residual)) return DL_ERR_ALIGN;
     Geometry g;
     const dl_status st = check_desc(d, &g);
     if (st != DL_OK) return st;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return DL_ERR_ALIGN;
     if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return DL_ERR_ALIGN;
     dlk::IgemmArgs a = fwd_args(d, g);
+    a.resid = static_cast<const uint16_t *>(residual);    // decides which kernels may take the launch
     const size_t need = igemm_scratch_bytes(a);
     if (need > 0 && (!workspace || workspace_bytes < need)) return DL_ERR_WORKSPACE;
     if (need > 0 && !aligned16(workspace)) return DL_ERR_ALIGN;
@@ -322,13 +333,20 @@ dl_status run_fwd(const dl_conv_desc *d, const void *x, const void *w, const flo
 dl_status conv2d_fwd(const dl_conv_desc *d, const void *x, const void *w, void *y, void *workspace,
                      size_t workspace_bytes, void *hip_stream)
 {
-    return run_fwd(d, x, w, nullptr, 0, y, workspace, workspace_bytes, hip_stream);
+    return run_fwd(d, x, w, nullptr, nullptr, 0, y, workspace, workspace_bytes, hip_stream);
 }
 
 dl_status conv2d_fwd_bias_relu(const dl_conv_desc *d, const void *x, const void *w, const float *bias, int32_t relu,
                                void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return run_fwd(d, x, w, bias, relu, y, workspace, workspace_bytes, hip_stream);
+    return run_fwd(d, x, w, bias, nullptr, relu, y, workspace, workspace_bytes, hip_stream);
+}
+
+dl_status conv2d_fwd_bias_add_relu(const dl_conv_desc *d, const void *x, const void *w, const float *bias,
+                                   const void *residual, int32_t relu, void *y, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    return run_fwd(d, x, w, bias, residual, relu, y, workspace, workspace_bytes, hip_stream);
 }
 
 dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, void *dx, void *workspace,

@@ -101,6 +101,24 @@ __device__ __forceinline__ floatx4_t apply_tail4(floatx4_t c, const float *bias,
     return c;
 }
 
+// c += resid[off .. off+3] (four consecutive columns col .. col+3 of one output row, those below ncols exist)
+template <class T>
+__device__ __forceinline__ floatx4_t add_resid4(floatx4_t c, const uint16_t *resid, size_t off, int col, int ncols)
+{
+    if (col + 3 < ncols && ((reinterpret_cast<uintptr_t>(resid + off) & 7) == 0)) {
+        const u32x2_t v = *reinterpret_cast<const u32x2_t *>(resid + off);
+        c[0] += T::to_float((uint16_t)(v[0] & 0xffffu));
+        c[1] += T::to_float((uint16_t)(v[0] >> 16));
+        c[2] += T::to_float((uint16_t)(v[1] & 0xffffu));
+        c[3] += T::to_float((uint16_t)(v[1] >> 16));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < ncols) c[e] += T::to_float(resid[off + e]);
+    }
+    return c;
+}
+
 // LDS tiles are [rows][BKT] 16-bit elements (BKT = 32 or 64) with the row
 // pitch padded by 8 elements (16 bytes): pitch/16 is then odd, so the 16-byte
 // fragment reads of 8 consecutive rows fall into 8 different 16-byte bank groups.

@@ -111,7 +111,10 @@ __global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
                 row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
             }
             const int col = n0 + wn * 32 + (lane & 31);
-            if (col < p.Nout) p.D[row_off + col] = T::from_float(apply_tail(acc[i][0][v], p.bias, p.relu, col));
+            if (col < p.Nout) {
+                const float r = p.resid ? T::to_float(p.resid[row_off + col]) : 0.f;
+                p.D[row_off + col] = T::from_float(apply_tail(acc[i][0][v] + r, p.bias, p.relu, col));
+            }
         }
 }
 
@@ -231,7 +234,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
                 hipError_t e = launch_igemm_dma(b, std::is_same<T, BF16>::value, 0, stream);      // 256 x 256 tiles
                 if (e != hipSuccess) return e;
                 return launch_splitk_reduce_tail(a.part, ks, M * a.Nout, a.D, std::is_same<T, BF16>::value ? 1 : 0, a.bias,
-                                                 a.relu, a.Nout, stream);
+                                                 a.relu, a.Nout, a.resid, stream);
             }
         }
         // A ragged last column tile of the widest configuration (e.g. 304 = 256 + 48 output
@@ -245,6 +248,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
             else hi.B = a.B + (size_t)lo.Nout * a.TR * a.TS * a.Cin;
             hi.D = a.D + lo.Nout;
             if (a.bias) hi.bias = a.bias + lo.Nout;
+            if (a.resid) hi.resid = a.resid + lo.Nout;
             hipError_t e = launch_igemm_dma(lo, std::is_same<T, BF16>::value, 0, stream);
             if (e != hipSuccess) return e;
             return launch_igemm_dma(hi, std::is_same<T, BF16>::value, rem <= 64 ? 3 : 2, stream);

@@ -311,12 +311,27 @@ __device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int til
     const bool tail = p.bias != nullptr || p.relu != 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        // a residual input is added here, before the rounding: this lane's row of it (8-byte reads)
+        size_t r_off = 0;
+        bool r_ok = false;
+        if (p.resid) {
+            const int m = m0 + (wm * TM + i) * 32 + (lane & 31);
+            r_ok = m < M;
+            if (dense) {
+                r_off = (size_t)m * p.ldd;
+            } else if (r_ok) {
+                const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+                const int oh = rem / p.OW, ow = rem - oh * p.OW;
+                r_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = lane & 31, ch = j * 32 + 8 * g + 4 * (lane >> 5);
                 floatx4_t c{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (r_ok) c = add_resid4<T>(c, p.resid, r_off + n0 + wn * CH + ch, n0 + wn * CH + ch, p.Nout);
                 if (tail) c = apply_tail4(c, p.bias, p.relu, n0 + wn * CH + ch, p.Nout);
                 u32x2_t pk;
                 pk[0] = (uint32_t)T::from_float(c[0]) | ((uint32_t)T::from_float(c[1]) << 16);

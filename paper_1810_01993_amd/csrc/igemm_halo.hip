@@ -231,7 +231,10 @@ __global__ __launch_bounds__(512) void igemm_halo_kernel(const IgemmArgs p)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-                if (col < p.Nout) p.D[row_off + col] = T::from_float(apply_tail(acc[i][j][v], p.bias, p.relu, col));
+                if (col < p.Nout) {
+                    const float r = p.resid ? T::to_float(p.resid[row_off + col]) : 0.f;
+                    p.D[row_off + col] = T::from_float(apply_tail(acc[i][j][v] + r, p.bias, p.relu, col));
+                }
             }
         }
     }

@@ -309,7 +309,7 @@ __global__ __launch_bounds__(512) void igemm_halo3x3_kernel(const IgemmArgs p, c
 bool igemm_halo3x3_applicable(const IgemmArgs &a)
 {
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
-    return dense && a.TR == 3 && a.TS == 3 && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0;
+    return dense && a.TR == 3 && a.TS == 3 && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0 && !a.resid;
 }
 
 static int64_t patches(const IgemmArgs &a)

@@ -374,7 +374,7 @@ bool igemm_narrow5x5_applicable(const IgemmArgs &a)
     }();
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && a.dth == 1 && a.dtw == 1 && a.Cin % 8 == 0 &&
-           a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && narrow_tiles(a) >= 128;
+           a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && !a.resid && narrow_tiles(a) >= 128;
 }
 
 // At most 32 input channels (one chunk), any number (a multiple of 4) of output columns, taps forward or mirrored.
@@ -386,7 +386,7 @@ bool igemm_wide5x5_applicable(const IgemmArgs &a)
     }();
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0 &&
-           a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && narrow_tiles(a) >= 128;
+           a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && !a.resid && narrow_tiles(a) >= 128;
 }
 
 hipError_t launch_igemm_wide5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream)

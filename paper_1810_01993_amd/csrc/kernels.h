@@ -45,6 +45,12 @@ struct IgemmArgs {
     // output column of THIS launch (null: none); relu != 0: negative results become zero.
     const float *bias;
     int32_t relu;
+    // ... + resid[same element as D] before the activation (the skip connection of a residual block):
+    // indexed exactly like D (a launch that offsets D by columns offsets resid alike); null: none.
+    // The kernels with an LDS-staged coalesced store that cannot reach it before rounding (3x3 halo-tile,
+    // narrow / wide 5x5) do not take such launches; the plain engine, the general halo-tile kernel, the
+    // streaming kernel for few input channels and the split reduction do.
+    const uint16_t *resid;
 };
 
 // Up to four GEMMs for one launch of the direct-to-LDS engine (see igemm_dma_batch_kernel).
@@ -181,7 +187,7 @@ hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n,
                                 hipStream_t stream);
 // The same with the forward convolution's point-wise tail: element i belongs to column i % ncols.
 hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
-                                     const float *bias, int32_t relu, int32_t ncols, hipStream_t stream);
+                                     const float *bias, int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream);
 
 // Backward of the point-wise tail y = max(s + bias, 0): dz = dy masked by y > 0 (relu != 0;
 // otherwise dz and y are not touched), dbias = column sums of dz.  partial: blocks x K floats.

@@ -34,10 +34,11 @@ __global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
         float a[THIN_MAX];
 #pragma unroll
         for (int c = 0; c < THIN_MAX; ++c) a[c] = c < p.Cin ? T::to_float(p.A[m * p.Cin + c]) : 0.f;
-        u32x4_t out;
+        u32x4_t out, rv{0, 0, 0, 0};
+        if (p.resid) rv = *reinterpret_cast<const u32x4_t *>(p.resid + m * p.ldd + j);
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            float s0 = 0.f, s1 = 0.f;
+            float s0 = T::to_float((uint16_t)(rv[e >> 1] & 0xffffu)), s1 = T::to_float((uint16_t)(rv[e >> 1] >> 16));
 #pragma unroll
             for (int c = 0; c < THIN_MAX; ++c) {
                 s0 += a[c] * b[e][c];

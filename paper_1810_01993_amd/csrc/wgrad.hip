@@ -236,7 +236,8 @@ hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 // only on `splits`, never on timing.
 template <int OUT>   // 0 f16, 1 bf16, 2 f32
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n,
-                                                            void *out, const float *__restrict__ bias, int relu, int ncols)
+                                                            void *out, const float *__restrict__ bias, int relu, int ncols,
+                                                            const uint16_t *__restrict__ resid)
 {
     __shared__ float part[4][64];
     const int x = threadIdx.x & 63, g = threadIdx.x >> 6;
@@ -257,6 +258,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
         __syncthreads();
         if (g == 0 && i < n) {
             float s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            if (OUT != 2 && resid) s += OUT == 1 ? BF16::to_float(resid[i]) : F16::to_float(resid[i]);   // same layout and type as out
             if (bias || relu) s = apply_tail(s, bias, relu, (int)(i % ncols));
             if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
             else if constexpr (OUT == 1) reinterpret_cast<uint16_t *>(out)[i] = BF16::from_float(s);
@@ -267,25 +269,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
-                                     const float *bias, int32_t relu, int32_t ncols, hipStream_t stream)
+                                     const float *bias, int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream)
 {
     if (n <= 0) return hipSuccess;
-    if (ncols < 1) return hipErrorInvalidValue;
+    if (ncols < 1 || (resid && out_dtype == 2)) return hipErrorInvalidValue;
     const int64_t want = (n + 63) / 64;
     const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
     if (out_dtype == 0)
-        hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+        hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else if (out_dtype == 1)
-        hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else
-        hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols);
+        hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                 hipStream_t stream)
 {
-    return launch_splitk_reduce_tail(partial, splits, n, out, out_dtype, nullptr, 0, 1, stream);
+    return launch_splitk_reduce_tail(partial, splits, n, out, out_dtype, nullptr, 0, 1, nullptr, stream);
 }
 
 }  // namespace dlk
