@@ -311,18 +311,39 @@ __device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int til
     const bool tail = p.bias != nullptr || p.relu != 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        // a residual input is added here, before the rounding: this lane's row of it (8-byte reads)
-        size_t r_off = 0;
-        bool r_ok = false;
+        // A residual input is added before the rounding.  Its 32-row slab is fetched the way the output is
+        // written (16 bytes per lane, whole rows of the wave's channel range) into the staging area, and every
+        // lane then picks up the four values that belong to its accumulators.
         if (p.resid) {
-            const int m = m0 + (wm * TM + i) * 32 + (lane & 31);
-            r_ok = m < M;
-            if (dense) {
-                r_off = (size_t)m * p.ldd;
-            } else if (r_ok) {
-                const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
-                const int oh = rem / p.OW, ow = rem - oh * p.OW;
-                r_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
+#pragma unroll
+            for (int it = 0; it < LPR / 2; ++it) {
+                const int row = it * (64 / LPR) + lane / LPR, c8 = (lane % LPR) * 8;
+                const int m = m0 + (wm * TM + i) * 32 + row;
+                const int col = n0 + wn * CH + c8;
+                u32x2_t lo{0, 0}, hi{0, 0};
+                if (m < M && col < p.Nout) {
+                    size_t row_off;
+                    if (dense) {
+                        row_off = (size_t)m * p.ldd;
+                    } else {
+                        const int n = m / (p.OH * p.OW), rem = m - n * (p.OH * p.OW);
+                        const int oh = rem / p.OW, ow = rem - oh * p.OW;
+                        row_off = ((size_t)(n * p.FH + oh * p.osh + p.ooh) * p.FW + ow * p.osw + p.oow) * p.ldd;
+                    }
+                    const uint16_t *src = p.resid + row_off + col;
+                    if (vec_ok && (reinterpret_cast<uintptr_t>(p.resid) & 15) == 0) {
+                        const u32x4_t v4 = *reinterpret_cast<const u32x4_t *>(src);
+                        lo[0] = v4[0]; lo[1] = v4[1]; hi[0] = v4[2]; hi[1] = v4[3];
+                    } else {
+                        uint32_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (col + e < p.Nout) w4[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
+                        lo[0] = w4[0]; lo[1] = w4[1]; hi[0] = w4[2]; hi[1] = w4[3];
+                    }
+                }
+                *reinterpret_cast<u32x2_t *>(stg + row * EP + c8) = lo;
+                *reinterpret_cast<u32x2_t *>(stg + row * EP + c8 + 4) = hi;
             }
         }
 #pragma unroll
@@ -331,7 +352,13 @@ __device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int til
             for (int g = 0; g < 4; ++g) {
                 const int row = lane & 31, ch = j * 32 + 8 * g + 4 * (lane >> 5);
                 floatx4_t c{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                if (r_ok) c = add_resid4<T>(c, p.resid, r_off + n0 + wn * CH + ch, n0 + wn * CH + ch, p.Nout);
+                if (p.resid) {
+                    const u32x2_t r = *reinterpret_cast<const u32x2_t *>(stg + row * EP + ch);
+                    c[0] += T::to_float((uint16_t)(r[0] & 0xffffu));
+                    c[1] += T::to_float((uint16_t)(r[0] >> 16));
+                    c[2] += T::to_float((uint16_t)(r[1] & 0xffffu));
+                    c[3] += T::to_float((uint16_t)(r[1] >> 16));
+                }
                 if (tail) c = apply_tail4(c, p.bias, p.relu, n0 + wn * CH + ch, p.Nout);
                 u32x2_t pk;
                 pk[0] = (uint32_t)T::from_float(c[0]) | ((uint32_t)T::from_float(c[1]) << 16);
