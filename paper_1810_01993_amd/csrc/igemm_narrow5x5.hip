@@ -24,6 +24,7 @@
 // same number of loads per wave (stand-ins go to a spare area), so one constant
 // wait count serves: when a step starts, everything but the newest filter slot
 // has landed.
+#include <algorithm>
 #include <cstdlib>
 
 #include "device_common.h"
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wide5x5_kernel(const IgemmArgs p
     const int ty = tile % tiles_y;
     const int img = tile / tiles_y;
     const int y0 = ty * N5_PH, x0 = tx * N5_PW;
-    const int ntiles_n = (p.Nout + BN - 1) / BN;
+    const int ntiles_n = (p.Nout + 63) / 64;
 
     const i32x4_t rsA = make_rsrc_words(p.A, (uint32_t)p.NB * p.IH * p.IW * p.Cin * 2u);
     const i32x4_t rsB = make_rsrc_words(p.B, (uint32_t)(N5_T * N5_T) * p.Nout * BK * 2u);
@@ -256,7 +257,9 @@ __global__ __launch_bounds__(256, 2) void igemm_wide5x5_kernel(const IgemmArgs p
     }
     // ---- the filter stream: step g = (column tile, column shift, row shift) -----------------
     // this wave's piece of a tap tile: rows (output columns) 16*wave + lrow of the column tile
-    int ld_ct = 0, ld_cs = 0, ld_tr = 0;
+    // (with few patches the column tiles are dealt over gridDim.y workgroups per patch: this one takes tiles
+    // blockIdx.y, blockIdx.y + gridDim.y, ...)
+    int ld_ct = blockIdx.y, ld_cs = 0, ld_tr = 0;
     auto issue_filter = [&](int slot) {
         const int jr = flip_r ? N5_T - 1 - ld_tr : ld_tr, js = flip_s ? N5_T - 1 - ld_cs : ld_cs;
         const int j = ld_ct * BN + 16 * wave + lrow;
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wide5x5_kernel(const IgemmArgs p
                      ok ? (uint32_t)(((jr * N5_T + js) * p.Nout + j) * BK + lane_c) * 2u : OOB_OFFSET);
         if (++ld_tr == N5_T) {
             ld_tr = 0;
-            if (++ld_cs == N5_T) { ld_cs = 0; ++ld_ct; }
+            if (++ld_cs == N5_T) { ld_cs = 0; ld_ct += gridDim.y; }
         }
     };
 
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wide5x5_kernel(const IgemmArgs p
 #pragma unroll
     for (int k = 0; k < S - 1; ++k) issue_filter(k);
     int slot = 0;
-    for (int ct = 0; ct < ntiles_n; ++ct) {
+    for (int ct = blockIdx.y; ct < ntiles_n; ct += gridDim.y) {
         const int nblk = min(KB, (p.Nout - ct * BN + 15) / 16);     // 16-column blocks of this tile that exist
 #pragma unroll
         for (int cs = 0; cs < N5_T; ++cs) {
@@ -386,15 +389,21 @@ bool igemm_wide5x5_applicable(const IgemmArgs &a)
     }();
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0 &&
-           a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && !a.resid && narrow_tiles(a) >= 128;
+           a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && !a.resid &&
+           narrow_tiles(a) * ((a.Nout + 63) / 64) >= 128;
 }
 
 hipError_t launch_igemm_wide5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
 {
     const int64_t tiles = narrow_tiles(a);
     if (!igemm_wide5x5_applicable(a) || tiles > 0x7fffffff || (reinterpret_cast<uintptr_t>(a.D) & 7) != 0) return hipErrorInvalidValue;
-    if (is_bf16) hipLaunchKernelGGL(igemm_wide5x5_kernel<BF16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(igemm_wide5x5_kernel<F16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
+    // enough workgroups for the chip (two per CU): with few patches the column tiles of a patch are dealt
+    // over several workgroups, each of which deposits the halo image for itself
+    const int ntiles_n = (a.Nout + 63) / 64;
+    const int per_patch = (int)std::min<int64_t>(ntiles_n, std::max<int64_t>(1, 512 / tiles));
+    const dim3 grid((unsigned)tiles, (unsigned)per_patch);
+    if (is_bf16) hipLaunchKernelGGL(igemm_wide5x5_kernel<BF16>, grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(igemm_wide5x5_kernel<F16>, grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
