@@ -84,7 +84,9 @@ size_t igemm_scratch_bytes(const dlk::IgemmArgs &a)
     if (!cols) return align_up(dlk::igemm_split_bytes(a), 256);
     dlk::IgemmArgs h = a;
     h.Nout = cols;
-    return align_up(dlk::igemm_blocked_filter_bytes(h), 256);
+    // (the 5x5 kernel for at most 32 output channels may split its reduction on small maps: partial sums behind the copy)
+    const size_t part = dlk::igemm_narrow5x5_applicable(h) ? align_up(dlk::igemm_narrow5x5_split_bytes(h), 256) : 0;
+    return align_up(dlk::igemm_blocked_filter_bytes(h), 256) + part;
 }
 
 // a.B: plain [Nout][taps*Cin] filter (may be null if the halo kernel takes every column).
@@ -105,6 +107,7 @@ hipError_t run_igemm(const dlk::IgemmArgs &a, bool bf16, const FilterSrc &fs, ui
     dlk::IgemmArgs h = a;
     h.Nout = cols;
     h.B = scratch;
+    h.part = reinterpret_cast<float *>(reinterpret_cast<char *>(scratch) + align_up(dlk::igemm_blocked_filter_bytes(h), 256));
     e = dlk::launch_igemm_halo(h, bf16, stream);
     if (e != hipSuccess || cols == a.Nout) return e;
     dlk::IgemmArgs r = a;

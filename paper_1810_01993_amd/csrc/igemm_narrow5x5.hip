@@ -54,6 +54,10 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nchunks = (p.Cin + BK - 1) / BK;
+    // Split reduction (maps with few patches): gridDim.y workgroups per patch, workgroup z takes the chunks
+    // [z * split_chunks, ...) and writes fp32 partial sums part[z][pixel][column] for the ordered reduce.
+    const int chunk_begin = p.ksplits > 1 ? (int)blockIdx.y * p.split_chunks : 0;
+    const int chunk_end = p.ksplits > 1 ? min(nchunks, chunk_begin + p.split_chunks) : nchunks;
 
     const int tiles_x = (p.OW + N5_PW - 1) / N5_PW, tiles_y = (p.OH + N5_PH - 1) / N5_PH;
     int tile = xcd_remap(blockIdx.x, gridDim.x);
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
         for (int a = 0; a < AW; ++a) {
             const int pc = wave + a * NW;
             const uint32_t dst = pc < HPIECES ? lds_addr(sH) + pc * 16 * BK * 2 : lds_addr(sSpare) + wave * 16 * BK * 2;
-            dma_load_16B(rsA, dst, (h_off[a] != OOB_OFFSET && lane_c < p.Cin - c0) ? h_off[a] + (uint32_t)c0 * 2u : OOB_OFFSET);
+            dma_load_16B(rsA, dst, (h_off[a] != OOB_OFFSET && chunk < chunk_end && lane_c < p.Cin - c0) ? h_off[a] + (uint32_t)c0 * 2u : OOB_OFFSET);
         }
     };
     auto issue_filter = [&](int g) {                     // column shift g % 5 of chunk g / 5, into slot g % 3
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
         for (int f = 0; f < FW; ++f) {
             const int pc = wave + f * NW;
             const uint32_t dst = pc < FPIECES ? lds_addr(sF + slot * F_ELEMS) + pc * 16 * BK * 2 : lds_addr(sSpare) + wave * 16 * BK * 2;
-            dma_load_16B(rsB, dst, (b_off[f] != OOB_OFFSET && chunk < nchunks) ? b_off[f] + base : OOB_OFFSET);
+            dma_load_16B(rsB, dst, (b_off[f] != OOB_OFFSET && chunk < chunk_end) ? b_off[f] + base : OOB_OFFSET);
         }
     };
 
@@ -121,11 +125,11 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
     const int foff = frow * BK + ((fsl ^ n5_swz(frow)) << 3);
     const int hbase = (wave * TM) * HW + frow;
 
-    issue_halo(0);
-    issue_filter(0);
-    issue_filter(1);
-    const int nsteps = nchunks * N5_T;
-    for (int g = 0, cs = 0; g < nsteps; ++g) {
+    issue_halo(chunk_begin);
+    issue_filter(chunk_begin * N5_T);
+    issue_filter(chunk_begin * N5_T + 1);
+    const int nsteps = chunk_end * N5_T;
+    for (int g = chunk_begin * N5_T, cs = 0; g < nsteps; ++g) {
         // everything but the newest filter slot has landed; every wave is past the previous step's reads
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(FW) : "memory");
@@ -174,6 +178,25 @@ __global__ __launch_bounds__(256, 2) void igemm_narrow5x5_kernel(const IgemmArgs
     // 16 bits, parks them in a private LDS area as [pixel][channel] (pitch 80 bytes: an odd number
     // of 16-byte units) and writes them out 16 bytes per lane; with 32 output channels a patch row
     // is one contiguous 2 KB run.
+    if (p.ksplits > 1) {
+        // fp32 partial sums, four consecutive channels per store; bias, activation and rounding happen in the reduce
+        const int64_t M = (int64_t)p.NB * p.OH * p.OW;
+        float *const out = p.part + (size_t)blockIdx.y * M * p.Nout;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int y = y0 + wave * TM + i, x = x0 + b * 16 + (lane & 15);
+                if (y >= p.OH || x >= p.OW) continue;
+                float *row = out + ((size_t)(img * p.OH + y) * p.OW + x) * p.Nout;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const int col = kb * 16 + 4 * (lane >> 4);
+                    if (col < p.Nout) *reinterpret_cast<floatx4_t *>(row + col) = acc[i][kb][b];     // Nout % 8 == 0
+                }
+            }
+        return;
+    }
     constexpr int EP = N5_BN + 8;
     static_assert((EP / 8) % 2 == 1 && NW * TM * N5_PW * EP <= H_ELEMS, "staging area");
     uint16_t *const stg = lds + wave * (TM * N5_PW) * EP;
@@ -367,6 +390,26 @@ static int64_t narrow_tiles(const IgemmArgs &a)
     return (int64_t)a.NB * ((a.OH + N5_PH - 1) / N5_PH) * ((a.OW + N5_PW - 1) / N5_PW);
 }
 
+// Maps with fewer than 128 patches: how many ranges the 32-channel chunks are cut into (1: no split) so that
+// the launch has about two workgroups per CU; *chunks_per_split: chunks per range.
+static int narrow_ksplits(const IgemmArgs &a, int *chunks_per_split)
+{
+    const int nchunks = (a.Cin + BK - 1) / BK;
+    const int64_t tiles = narrow_tiles(a);
+    int ks = 1;
+    if (tiles < 128 && a.ldd == a.Nout) ks = (int)std::min<int64_t>(nchunks, (512 + tiles - 1) / tiles);
+    const int cps = (nchunks + ks - 1) / ks;
+    ks = (nchunks + cps - 1) / cps;                      // no empty range
+    if (chunks_per_split) *chunks_per_split = cps;
+    return ks;
+}
+
+size_t igemm_narrow5x5_split_bytes(const IgemmArgs &a)
+{
+    const int ks = narrow_ksplits(a, nullptr);
+    return ks > 1 ? (size_t)ks * a.NB * a.OH * a.OW * a.Nout * sizeof(float) : 0;
+}
+
 // Forward-oriented taps only (a data gradient of such a layer has 32 INPUT channels and many
 // output columns: not this kernel's shape).
 bool igemm_narrow5x5_applicable(const IgemmArgs &a)
@@ -377,7 +420,8 @@ bool igemm_narrow5x5_applicable(const IgemmArgs &a)
     }();
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && a.dth == 1 && a.dtw == 1 && a.Cin % 8 == 0 &&
-           a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && !a.resid && narrow_tiles(a) >= 128;
+           a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && !a.resid &&
+           narrow_tiles(a) * narrow_ksplits(a, nullptr) >= 128;
 }
 
 // At most 32 input channels (one chunk), any number (a multiple of 4) of output columns, taps forward or mirrored.
@@ -411,9 +455,19 @@ hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t 
 {
     const int64_t tiles = narrow_tiles(a);
     if (!igemm_narrow5x5_applicable(a) || tiles > 0x7fffffff || (reinterpret_cast<uintptr_t>(a.D) & 15) != 0) return hipErrorInvalidValue;
-    if (is_bf16) hipLaunchKernelGGL(igemm_narrow5x5_kernel<BF16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(igemm_narrow5x5_kernel<F16>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    IgemmArgs b = a;
+    int cps = 0;
+    const int ks = narrow_ksplits(a, &cps);
+    b.ksplits = ks;
+    b.split_chunks = cps;
+    if (ks > 1 && !a.part) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)tiles, (unsigned)ks);
+    if (is_bf16) hipLaunchKernelGGL(igemm_narrow5x5_kernel<BF16>, grid, dim3(256), 0, stream, b);
+    else hipLaunchKernelGGL(igemm_narrow5x5_kernel<F16>, grid, dim3(256), 0, stream, b);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || ks == 1) return e;
+    return launch_splitk_reduce_tail(a.part, ks, (int64_t)a.NB * a.OH * a.OW * a.Nout, a.D, is_bf16 ? 1 : 0, a.bias, a.relu,
+                                     a.Nout, nullptr, stream);
 }
 
 }  // namespace dlk

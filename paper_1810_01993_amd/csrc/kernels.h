@@ -85,6 +85,8 @@ int igemm_halo_columns(const IgemmArgs &a);
 // Dense 5x5, unit stride and dilation, forward-oriented taps, 8..32 output columns (a multiple of 8), D 16-byte
 // aligned: one 32-wide column tile per 16 x 32 pixel patch; a.B as for the other halo-tile kernels.
 bool igemm_narrow5x5_applicable(const IgemmArgs &a);
+// fp32 scratch (a.part) the launch needs when it splits the reduction (maps with few patches), else 0
+size_t igemm_narrow5x5_split_bytes(const IgemmArgs &a);
 hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 // The mirror case: dense 5x5, unit stride and dilation, taps forward or mirrored, at most 32 input channels (one
 // chunk), more than 32 output columns (a multiple of 4), D 8-byte aligned: the data gradient of such a layer.

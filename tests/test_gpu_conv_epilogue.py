@@ -73,6 +73,7 @@ CASES = [
     (L("e.stem7x7", 2, 30, 44, 16, 64, 7, 7, 2, 3, 1), "bf16"),
     (L("e.narrow5x5.k32", 4, 75, 200, 16, 32, 5, 5, 1, 2, 1), "f16"),             # 5x5 kernel for <= 32 output channels
     (L("e.narrow5x5.k24", 3, 100, 230, 40, 24, 5, 5, 1, 2, 1), "bf16"),
+    (L("e.narrow5x5.ksplit", 4, 50, 70, 96, 32, 5, 5, 1, 2, 1), "f16"),             # its split reduction: tail in the reduce kernel
 ]
 
 

@@ -54,6 +54,9 @@ NARROW = [
     (L("tira.narrow.c72.k24", 3, 100, 230, 72, 24, 5, 5, 1, 2, 1), "f16"),
     (L("tira.narrow.c48.pad1", 2, 130, 260, 48, 32, 5, 5, 1, 1, 1), "bf16"),       # output 128 x 258
     (L("tira.narrow.c8.k8.pad4", 2, 120, 250, 8, 8, 5, 5, 1, 4, 1), "f16"),        # output 124 x 254, taps deep in the padding
+    # few patches: the 32-channel chunks are split over workgroups (fp32 partial sums + ordered reduce)
+    (L("tira.narrow.ksplit.c96", 4, 50, 70, 96, 32, 5, 5, 1, 2, 1), "f16"),         # 48 patches x 3 ranges, element by element
+    (L("tira.narrow.ksplit.c200.k24", 2, 90, 100, 200, 24, 5, 5, 1, 2, 1), "bf16"), # 7 chunks (the last of 8 channels) in 7 ranges
 ]
 
 
