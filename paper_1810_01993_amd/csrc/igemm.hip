@@ -193,7 +193,11 @@ static int choose_cfg(const IgemmArgs &a)
     auto blocks = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((a.Nout + bn - 1) / bn); };
     if (nmax <= 32 || a.Nout <= 32) return 104;                     // 64 x 32
     if (nmax >= 256 && blocks(256, 256) >= 200) return 100;         // 256 x 256
-    if (nmax >= 128 && blocks(128, 128) >= 400) return 102;         // 128 x 128
+    static const int min128 = [] {
+        const char *e = std::getenv("DLCONV_CFG128_MIN");   // tuning override: fewest 128 x 128 tiles that configuration is used for
+        return e ? std::atoi(e) : 200;
+    }();
+    if (nmax >= 128 && blocks(128, 128) >= min128) return 102;      // 128 x 128
     if (blocks(128, 64) >= 200) return 103;                         // 128 x 64
     return 108;                                                     // 64 x 64
 }
