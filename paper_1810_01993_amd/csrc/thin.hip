@@ -11,45 +11,61 @@ namespace dlk {
 constexpr int THIN_MAX = 4;      // channels on the thin side
 
 // D[m][j..j+7] = sum_{c < Cin} A[m][c] * B[j..j+7][c]   (one tap, dense rows, Cin <= THIN_MAX, Nout % 8 == 0)
-// A thread owns one group of 8 output columns, keeps their filter values in
-// registers and walks down the rows: one 16-byte store per Cin broadcast loads.
+// A thread owns one group of 8 output columns and keeps their filter values in registers.  A workgroup owns a
+// contiguous range of rows, fetches their A values (Cin per row) coalesced into LDS, SUB rows at a time, and
+// walks down them: one 16-byte store per Cin LDS broadcast reads, no global load between two stores (with the
+// A values read from memory row by row the sweep took 0.30 instead of 0.23 ms on the logits layer whenever
+// other kernels had run since the last call, as in a training step).
 template <class T>
 __global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
 {
+    constexpr int SUB = 512;
+    __shared__ float sa[SUB * THIN_MAX];
     const int groups = p.Nout / 8;
-    const int gpb = groups < 256 ? groups : 256;         // column groups per workgroup
-    const int rows_pb = 256 / gpb;                       // rows per workgroup pass
+    const int gpb = groups < 256 ? groups : 256;
+    const int rows_pb = 256 / gpb;
     const int g = blockIdx.y * gpb + threadIdx.x % gpb, r = threadIdx.x / gpb;
-    if (r >= rows_pb || g >= groups) return;
-    const int j = g * 8;
+    const bool active = r < rows_pb && g < groups;
+    const int j = active ? g * 8 : 0;
     float b[8][THIN_MAX];
 #pragma unroll
     for (int e = 0; e < 8; ++e)
 #pragma unroll
         for (int c = 0; c < THIN_MAX; ++c) b[e][c] = c < p.Cin ? T::to_float(p.B[(size_t)(j + e) * p.Cin + c]) : 0.f;
     const int64_t M = (int64_t)p.NB * p.OH * p.OW;
-    const int64_t step = (int64_t)gridDim.x * rows_pb;
-#pragma unroll 4
-    for (int64_t m = (int64_t)blockIdx.x * rows_pb + r; m < M; m += step) {
-        float a[THIN_MAX];
-#pragma unroll
-        for (int c = 0; c < THIN_MAX; ++c) a[c] = c < p.Cin ? T::to_float(p.A[m * p.Cin + c]) : 0.f;
-        u32x4_t out, rv{0, 0, 0, 0};
-        if (p.resid) rv = *reinterpret_cast<const u32x4_t *>(p.resid + m * p.ldd + j);
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            float s0 = T::to_float((uint16_t)(rv[e >> 1] & 0xffffu)), s1 = T::to_float((uint16_t)(rv[e >> 1] >> 16));
-#pragma unroll
-            for (int c = 0; c < THIN_MAX; ++c) {
-                s0 += a[c] * b[e][c];
-                s1 += a[c] * b[e + 1][c];
-            }
-            s0 = apply_tail(s0, p.bias, p.relu, j + e);
-            s1 = apply_tail(s1, p.bias, p.relu, j + e + 1);
-            out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+    const int64_t chunk = (M + gridDim.x - 1) / gridDim.x;
+    const int64_t m_begin = (int64_t)blockIdx.x * chunk, m_end = m_begin + chunk < M ? m_begin + chunk : M;
+    for (int64_t sub = m_begin; sub < m_end; sub += SUB) {
+        const int n = (int)(m_end - sub < SUB ? m_end - sub : SUB);
+        __syncthreads();
+        for (int i = threadIdx.x; i < n * p.Cin; i += 256) {
+            const int row = i / p.Cin, c = i - row * p.Cin;
+            sa[row * THIN_MAX + c] = T::to_float(p.A[sub * p.Cin + i]);
         }
-        // streamed store: the output (0.9 GB for the logits layer) is far larger than the caches
-        __builtin_nontemporal_store(out, reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j));
+        __syncthreads();
+        if (!active) continue;
+#pragma unroll 4
+        for (int q = r; q < n; q += rows_pb) {
+            const int64_t m = sub + q;
+            float a[THIN_MAX];
+#pragma unroll
+            for (int c = 0; c < THIN_MAX; ++c) a[c] = c < p.Cin ? sa[q * THIN_MAX + c] : 0.f;
+            u32x4_t out, rv{0, 0, 0, 0};
+            if (p.resid) rv = *reinterpret_cast<const u32x4_t *>(p.resid + m * p.ldd + j);
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                float s0 = T::to_float((uint16_t)(rv[e >> 1] & 0xffffu)), s1 = T::to_float((uint16_t)(rv[e >> 1] >> 16));
+#pragma unroll
+                for (int c = 0; c < THIN_MAX; ++c) {
+                    s0 += a[c] * b[e][c];
+                    s1 += a[c] * b[e + 1][c];
+                }
+                s0 = apply_tail(s0, p.bias, p.relu, j + e);
+                s1 = apply_tail(s1, p.bias, p.relu, j + e + 1);
+                out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j));
+        }
     }
 }
 
@@ -67,8 +83,13 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
     const int groups = a.Nout / 8;
     if (M <= 0 || groups <= 0) return hipSuccess;
     const int gpb = groups < 256 ? groups : 256, rows_pb = 256 / gpb;
-    const int64_t want = (M + rows_pb * 48 - 1) / (rows_pb * 48);   // about 48 rows per thread
-    const dim3 grid((unsigned)(want < 32768 ? want : 32768), (unsigned)((groups + gpb - 1) / gpb)), block(256);
+    // 512 rows per workgroup (best of 64..4096 on the logits layer); fewer when that would leave compute units idle
+    int64_t per = (M + 1023) / 1024;
+    per = (per + rows_pb - 1) / rows_pb * rows_pb;
+    if (per < 4 * rows_pb) per = 4 * rows_pb;
+    if (per > 512) per = 512;
+    const int64_t wg = (M + per - 1) / per;
+    const dim3 grid((unsigned)(wg < 65535 ? wg : 65535), (unsigned)((groups + gpb - 1) / gpb)), block(256);
     if (is_bf16) hipLaunchKernelGGL(thin_rows_kernel<BF16>, grid, block, 0, stream, a);
     else hipLaunchKernelGGL(thin_rows_kernel<F16>, grid, block, 0, stream, a);
     return hipGetLastError();
