@@ -229,35 +229,46 @@ hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 }
 
 // ---- ordered reduction of the split partials ------------------------------
-// Workgroup = 64 outputs x 4 slice groups.  Thread (x, g) adds slices g, g+4,
-// g+8, ... in ascending order with four independent running sums (so that
-// several loads are in flight), combines them in a fixed order, and the four
-// groups are then added in ascending g through LDS: the summation tree depends
-// only on `splits`, never on timing.
-template <int OUT>   // 0 f16, 1 bf16, 2 f32
+// Workgroup = XW outputs x G slice groups (XW * G = 256).  Thread (x, g) adds
+// slices g, g+G, g+2G, ... in ascending order with four independent running
+// sums (so that several loads are in flight), combines them in a fixed order,
+// and the G groups are then added in ascending g through LDS: the summation
+// tree depends only on `splits` and G, never on timing.  G = 4 in general;
+// G = 32 for the few-outputs, many-slices case (the thin filter gradient:
+// 768 outputs x 2048 slices), where 4 groups would leave each thread a chain
+// of 128 dependent round trips.
+template <int OUT, int G>   // OUT: 0 f16, 1 bf16, 2 f32
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t n,
                                                             void *out, const float *__restrict__ bias, int relu, int ncols,
                                                             const uint16_t *__restrict__ resid)
 {
-    __shared__ float part[4][64];
-    const int x = threadIdx.x & 63, g = threadIdx.x >> 6;
-    for (int64_t base = (int64_t)blockIdx.x * 64; base < n; base += (int64_t)gridDim.x * 64) {
+    constexpr int XW = 256 / G;
+    __shared__ float part[G][XW];
+    const int x = threadIdx.x % XW, g = threadIdx.x / XW;
+    for (int64_t base = (int64_t)blockIdx.x * XW; base < n; base += (int64_t)gridDim.x * XW) {
         const int64_t i = base + x;
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
         if (i < n) {
             int z = g;
-            for (; z + 12 < splits; z += 16) {
+            for (; z + 3 * G < splits; z += 4 * G) {
                 s0 += partial[(size_t)z * n + i];
-                s1 += partial[(size_t)(z + 4) * n + i];
-                s2 += partial[(size_t)(z + 8) * n + i];
-                s3 += partial[(size_t)(z + 12) * n + i];
+                s1 += partial[(size_t)(z + G) * n + i];
+                s2 += partial[(size_t)(z + 2 * G) * n + i];
+                s3 += partial[(size_t)(z + 3 * G) * n + i];
             }
-            for (; z < splits; z += 4) s0 += partial[(size_t)z * n + i];
+            for (; z < splits; z += G) s0 += partial[(size_t)z * n + i];
         }
         part[g][x] = (s0 + s1) + (s2 + s3);
         __syncthreads();
         if (g == 0 && i < n) {
-            float s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            float s;
+            if constexpr (G == 4) {
+                s = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            } else {
+                s = 0.f;
+#pragma unroll
+                for (int q = 0; q < G; q += 4) s += (part[q][x] + part[q + 1][x]) + (part[q + 2][x] + part[q + 3][x]);
+            }
             if (OUT != 2 && resid) s += OUT == 1 ? BF16::to_float(resid[i]) : F16::to_float(resid[i]);   // same layout and type as out
             if (bias || relu) s = apply_tail(s, bias, relu, (int)(i % ncols));
             if constexpr (OUT == 0) reinterpret_cast<uint16_t *>(out)[i] = F16::from_float(s);
@@ -268,20 +279,29 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
+template <int G>
+static hipError_t launch_reduce_g(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype, const float *bias,
+                                  int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream)
+{
+    constexpr int XW = 256 / G;
+    const int64_t want = (n + XW - 1) / XW;
+    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
+    if (out_dtype == 0)
+        hipLaunchKernelGGL((splitk_reduce_kernel<0, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+    else if (out_dtype == 1)
+        hipLaunchKernelGGL((splitk_reduce_kernel<1, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<2, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
+    return hipGetLastError();
+}
+
 hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
                                      const float *bias, int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream)
 {
     if (n <= 0) return hipSuccess;
     if (ncols < 1 || (resid && out_dtype == 2)) return hipErrorInvalidValue;
-    const int64_t want = (n + 63) / 64;
-    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
-    if (out_dtype == 0)
-        hipLaunchKernelGGL(splitk_reduce_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
-    else if (out_dtype == 1)
-        hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
-    else
-        hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
-    return hipGetLastError();
+    if (splits >= 128 && n <= 8192) return launch_reduce_g<32>(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
+    return launch_reduce_g<4>(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
 }
 
 hipError_t launch_splitk_reduce(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,
