@@ -8,6 +8,8 @@
 // 8 x (4 pixels) and writes 8-byte pieces into a [channel][pixel] LDS tile.
 // The pixel range is cut into `splits` slices (grid.y); every slice writes an
 // fp32 partial tile, and a second kernel adds the slices in a fixed order.
+#include <cstdint>
+#include <cstdlib>
 #include "device_common.h"
 #include "kernels.h"
 
@@ -279,6 +281,72 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
+// The G = 4 reduction with four consecutive outputs per thread (16-byte loads of the partial sums, n % 4 == 0):
+// every output is summed in exactly the order of the kernel above, so the two give identical bits.
+template <int OUT>
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float *__restrict__ partial, int splits, int64_t n,
+                                                             void *out, const float *__restrict__ bias, int relu, int ncols,
+                                                             const uint16_t *__restrict__ resid)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ f4 part[4][64];
+    const int x = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int64_t base = (int64_t)blockIdx.x * 256; base < n; base += (int64_t)gridDim.x * 256) {
+        const int64_t i = base + 4 * x;
+        f4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+        if (i < n) {
+            int z = g;
+            for (; z + 12 < splits; z += 16) {
+                s0 += *reinterpret_cast<const f4 *>(partial + (size_t)z * n + i);
+                s1 += *reinterpret_cast<const f4 *>(partial + (size_t)(z + 4) * n + i);
+                s2 += *reinterpret_cast<const f4 *>(partial + (size_t)(z + 8) * n + i);
+                s3 += *reinterpret_cast<const f4 *>(partial + (size_t)(z + 12) * n + i);
+            }
+            for (; z < splits; z += 4) s0 += *reinterpret_cast<const f4 *>(partial + (size_t)z * n + i);
+        }
+        part[g][x] = (s0 + s1) + (s2 + s3);
+        __syncthreads();
+        if (g == 0 && i < n) {
+            const f4 v = (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+            float s[4] = {v[0], v[1], v[2], v[3]};
+            if (OUT != 2 && resid) {
+                const uint2 rv = *reinterpret_cast<const uint2 *>(resid + i);
+                const uint16_t r[4] = {(uint16_t)(rv.x & 0xffffu), (uint16_t)(rv.x >> 16), (uint16_t)(rv.y & 0xffffu), (uint16_t)(rv.y >> 16)};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] += OUT == 1 ? BF16::to_float(r[e]) : F16::to_float(r[e]);
+            }
+            if (bias || relu) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] = apply_tail(s[e], bias, relu, (int)((i + e) % ncols));
+            }
+            if constexpr (OUT == 2) {
+                *reinterpret_cast<f4 *>(reinterpret_cast<float *>(out) + i) = f4{s[0], s[1], s[2], s[3]};
+            } else {
+                uint16_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = OUT == 1 ? BF16::from_float(s[e]) : F16::from_float(s[e]);
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + i) =
+                    uint2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+            }
+        }
+        __syncthreads();
+    }
+}
+
+static hipError_t launch_reduce4(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype, const float *bias,
+                                 int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream)
+{
+    const int64_t want = (n + 255) / 256;
+    const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
+    if (out_dtype == 0)
+        hipLaunchKernelGGL(splitk_reduce4_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+    else if (out_dtype == 1)
+        hipLaunchKernelGGL(splitk_reduce4_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+    else
+        hipLaunchKernelGGL(splitk_reduce4_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
+    return hipGetLastError();
+}
+
 template <int G>
 static hipError_t launch_reduce_g(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype, const float *bias,
                                   int32_t relu, int32_t ncols, const uint16_t *resid, hipStream_t stream)
@@ -301,6 +369,14 @@ hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64
     if (n <= 0) return hipSuccess;
     if (ncols < 1 || (resid && out_dtype == 2)) return hipErrorInvalidValue;
     if (splits >= 128 && n <= 8192) return launch_reduce_g<32>(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
+    static const int vec = [] {
+        const char *e = std::getenv("DLCONV_REDUCE4");        // tuning override: 0 = one output per thread always
+        return e ? std::atoi(e) : 1;
+    }();
+    const bool aligned = (reinterpret_cast<uintptr_t>(partial) % 16 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(resid) % 8 == 0);
+    if (vec && n % 4 == 0 && n >= 65536 && aligned)
+        return launch_reduce4(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
     return launch_reduce_g<4>(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
 }
 
