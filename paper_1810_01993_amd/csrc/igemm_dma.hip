@@ -399,6 +399,14 @@ __device__ __forceinline__ void igemm_dma_tile(const IgemmArgs &p, const int til
 template <class T, int BM, int BN, int WM, int WN, bool CMAJOR, bool BT = false>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_dma_kernel(const IgemmArgs p)
 {
+    // Split reduction into 2, 4 or 8 ranges: range s runs on the XCDs s, s + ranges, ... (workgroups are dealt to the
+    // eight XCDs in turn, x fastest), so that an XCD's L2 holds one range of the channels of both operands
+    // instead of all of them (ASPP 3x3 forward: 4.7 MB per XCD instead of 37 MB).
+    if (gridDim.y > 1 && 8 % gridDim.y == 0) {
+        const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
+        igemm_dma_tile<T, BM, BN, WM, WN, CMAJOR, BT>(p, (int)(id / gridDim.y), (int)(id % gridDim.y));
+        return;
+    }
     igemm_dma_tile<T, BM, BN, WM, WN, CMAJOR, BT>(p, xcd_remap(blockIdx.x, gridDim.x), blockIdx.y);
 }
 
