@@ -86,6 +86,7 @@ SMALL = [
     L("1x1", 2, 17, 19, 72, 136, 1, 1, 1, 0, 1),
     L("1x1.s2", 2, 18, 20, 64, 160, 1, 1, 2, 0, 1),
     L("1x1.k3", 1, 33, 47, 256, 3, 1, 1, 1, 0, 1),
+    L("1x1.k3.many-slices", 1, 150, 250, 64, 3, 1, 1, 1, 0, 1),   # 147 pixel slices x 192 outputs: the 32-group reduce; ragged row ranges
     L("1x1.k48", 1, 20, 30, 256, 48, 1, 1, 1, 0, 1),
     L("1x1.k4.c304", 2, 21, 30, 304, 4, 1, 1, 1, 0, 1),
     L("1x1.k2.c8", 1, 9, 10, 8, 2, 1, 1, 1, 0, 1),
