@@ -393,13 +393,25 @@ dl_status conv2d_bwd_data(const dl_conv_desc *d, const void *dy, const void *w, 
     int n_pending = 0;
     bool overflow = false;
     size_t ws_off = 0;
+    // classes that no tap reaches (e.g. three of the four of a 1x1 stride-2 layer) are all zeros: one fill for all
+    uint64_t zero_mask = 0;
+    if (d->C % 8 == 0 && d->stride_h * d->stride_w <= 64) {
+        for (int ca = 0; ca < d->stride_h; ++ca)
+            for (int cb = 0; cb < d->stride_w; ++cb) {
+                const DgradClass c = dgrad_class(d, g, ca, cb);
+                if (!c.empty && !c.has_taps) zero_mask |= 1ull << (ca * d->stride_w + cb);
+            }
+        if (zero_mask && dlk::launch_zero_classes(static_cast<uint16_t *>(dx), d->N, d->H, d->W, d->C, d->stride_h, d->stride_w,
+                                                  zero_mask, stream) != hipSuccess)
+            return DL_ERR_LAUNCH;
+    }
     for (int ca = 0; ca < d->stride_h; ++ca)
         for (int cb = 0; cb < d->stride_w; ++cb) {
             DgradClass c = dgrad_class(d, g, ca, cb);
             uint16_t *wt = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + ws_off);
             uint16_t *blk = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + ws_off + c.wt_bytes);
             ws_off += c.wt_bytes + c.blk_bytes;
-            if (c.empty) continue;
+            if (c.empty || ((zero_mask >> (ca * d->stride_w + cb)) & 1)) continue;
             dlk::IgemmArgs &a = c.args;
             a.A = static_cast<const uint16_t *>(dy);
             a.D = static_cast<uint16_t *>(dx);

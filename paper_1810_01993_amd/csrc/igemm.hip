@@ -324,6 +324,30 @@ __global__ void filter_relayout_kernel(const FilterRelayoutArgs p)
     }
 }
 
+// Zero fill of the input-gradient pixels that no filter tap reaches (a 1x1 filter with stride 2 reads one pixel
+// in four): pixel (h, w) belongs to stride-parity class (h % sh) * sw + (w % sw); the classes whose bit is set in
+// `mask` are cleared, 16 bytes per thread, all of them in one sweep over the tensor (C % 8 == 0).
+__global__ __launch_bounds__(256) void zero_classes_kernel(uint16_t *__restrict__ dx, int64_t pieces, int H, int W, int C8, int sh,
+                                                           int sw, uint64_t mask)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pieces; i += (int64_t)gridDim.x * 256) {
+        const int64_t pix = i / C8;
+        const int w = (int)(pix % W), h = (int)((pix / W) % H);
+        if ((mask >> ((h % sh) * sw + (w % sw))) & 1) *reinterpret_cast<u32x4_t *>(dx + i * 8) = u32x4_t{0, 0, 0, 0};
+    }
+}
+
+hipError_t launch_zero_classes(uint16_t *dx, int N, int H, int W, int C, int sh, int sw, uint64_t mask, hipStream_t stream)
+{
+    if (C % 8 != 0 || sh < 1 || sw < 1 || sh * sw > 64) return hipErrorInvalidValue;
+    const int64_t pieces = (int64_t)N * H * W * (C / 8);
+    if (pieces <= 0 || mask == 0) return hipSuccess;
+    const int64_t want = (pieces + 256 * 8 - 1) / (256 * 8);          // about eight pieces per thread
+    const dim3 grid((unsigned)(want < 65535 ? want : 65535)), block(256);
+    hipLaunchKernelGGL(zero_classes_kernel, grid, block, 0, stream, dx, pieces, H, W, C / 8, sh, sw, mask);
+    return hipGetLastError();
+}
+
 hipError_t launch_filter_relayout(const FilterRelayoutArgs &a, hipStream_t stream)
 {
     const int64_t total = (int64_t)a.C * a.TR * a.TS * a.K;

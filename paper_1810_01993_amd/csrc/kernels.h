@@ -130,6 +130,9 @@ struct FilterRelayoutArgs {
     int32_t r0, rstep, TR, s0, sstep, TS;
 };
 hipError_t launch_filter_relayout(const FilterRelayoutArgs &a, hipStream_t stream);
+// Clears the pixels of dx[N][H][W][C] (C % 8 == 0, sh * sw <= 64) whose stride-parity class (h % sh) * sw + (w % sw)
+// has its bit set in `mask`.
+hipError_t launch_zero_classes(uint16_t *dx, int N, int H, int W, int C, int sh, int sw, uint64_t mask, hipStream_t stream);
 
 // Filter gradient: partial[z][k][j] = sum over the z-th slice of the N*P*Q
 // pixels of dy[pix][k] * x[pixel(pix, tap(j)), c(j)],  j = (r*S + s)*C + c.
