@@ -206,6 +206,21 @@ dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uin
                                     float *loss, void *dlogits,
                                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* weighted_pixel_ce_fwd_bwd for callers that cannot allocate device memory or
+ * carry a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same bits; the per-workgroup partial sums live in a 4 KB array that
+ * the library itself holds on every GPU it runs on (resolved on the first call
+ * on a device; the call allocates and frees nothing).  Limit: n_pixels <=
+ * DL_CE_STATIC_MAX_PIXELS, DL_ERR_SHAPE beyond.  All calls on one GPU share
+ * that array: calls that may overlap on one GPU (different streams without an
+ * ordering between them, several host threads) race on it and must be ordered
+ * by the caller; nothing in it has to survive from one call to the next. */
+#define DL_CE_STATIC_MAX_PIXELS 1073741824LL   /* 2^30 */
+dl_status weighted_pixel_ce_fwd_bwd_static(const void *logits, int32_t dtype, const uint8_t *labels,
+                                           const float *class_weights, float scale, int64_t n_pixels,
+                                           float *loss, void *dlogits, void *hip_stream);
+
 /* The same loss with the weight given per pixel (paper, Sec. "Weighted loss":
  * the per-pixel weight map is computed by the input pipeline and handed to the
  * GPU with the image): weight_map[i] stands where class_weights[label_i]

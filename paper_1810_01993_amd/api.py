@@ -21,7 +21,8 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
 EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_fwd_bias_add_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
-           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd",
+           "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_fwd_bwd_static",
+           "weighted_pixel_ce_map_fwd_bwd",
            "dl_logits_ce_workspace_bytes", "logits_ce_fused_fwd_bwd", "dl_status_string")
 
 
@@ -84,6 +85,7 @@ def _load() -> ctypes.CDLL:
     lib.dl_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.POINTER(sz)]
     for name in ("weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_map_fwd_bwd"):
         getattr(lib, name).argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp, sz, vp]
+    lib.weighted_pixel_ce_fwd_bwd_static.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, vp, vp, vp]
     lib.dl_logits_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.logits_ce_fused_fwd_bwd.argtypes = [vp, vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, ctypes.c_int32,
                                             vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp]
@@ -375,6 +377,26 @@ def weighted_pixel_ce_fwd_bwd(logits: torch.Tensor, labels: torch.Tensor, class_
                                           _dev_ptr(class_weights), ctypes.c_float(scale), n, _dev_ptr(loss),
                                           _dev_ptr(dlogits), _dev_ptr(ws), nb, _stream()),
            "weighted_pixel_ce_fwd_bwd")
+    return loss, dlogits
+
+
+CE_STATIC_MAX_PIXELS = 1 << 30
+
+
+def weighted_pixel_ce_fwd_bwd_static(logits: torch.Tensor, labels: torch.Tensor, class_weights: torch.Tensor,
+                                     scale: float, loss: torch.Tensor, dlogits: torch.Tensor):
+    """``weighted_pixel_ce_fwd_bwd`` without a workspace and without any allocation, here or in the
+    library: the caller brings every buffer (loss float32[1], dlogits like logits)."""
+    n = labels.numel()
+    if logits.shape[-1] != 3 or logits.numel() != 3 * n or labels.dtype != torch.uint8:
+        raise ValueError("logits [..., 3] and uint8 labels with one entry per pixel expected")
+    if class_weights.dtype != torch.float32 or class_weights.numel() != 3 or loss.dtype != torch.float32:
+        raise ValueError("class_weights must be float32[3], loss float32[1]")
+    if dlogits.dtype != logits.dtype or dlogits.numel() != logits.numel():
+        raise ValueError("dlogits must match logits")
+    _check(_lib.weighted_pixel_ce_fwd_bwd_static(_dev_ptr(logits), _dtype_code(logits), _dev_ptr(labels),
+                                                 _dev_ptr(class_weights), ctypes.c_float(scale), n, _dev_ptr(loss),
+                                                 _dev_ptr(dlogits), _stream()), "weighted_pixel_ce_fwd_bwd_static")
     return loss, dlogits
 
 

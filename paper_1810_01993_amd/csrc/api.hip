@@ -641,6 +641,23 @@ dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uin
                   workspace_bytes, hip_stream);
 }
 
+dl_status weighted_pixel_ce_fwd_bwd_static(const void *logits, int32_t dtype, const uint8_t *labels,
+                                           const float *class_weights, float scale, int64_t n_pixels, float *loss,
+                                           void *dlogits, void *hip_stream)
+{
+    // the same checks as the entry point with a workspace, then the size limit of this one
+    if (!loss || !class_weights) return DL_ERR_NULL;
+    if (n_pixels < 0 || n_pixels > DL_CE_STATIC_MAX_PIXELS) return DL_ERR_SHAPE;
+    if (n_pixels > 0 && (!logits || !labels || !dlogits)) return DL_ERR_NULL;
+    if (dtype != DL_F16 && dtype != DL_BF16) return DL_ERR_DTYPE;
+    if (!aligned16(logits) || !aligned16(labels) || !aligned16(dlogits)) return DL_ERR_ALIGN;
+    float *partials = nullptr;
+    if (dlk::ce_static_partials(&partials) != hipSuccess) return DL_ERR_LAUNCH;
+    return hip_status(dlk::launch_weighted_ce(static_cast<const uint16_t *>(logits), dtype == DL_BF16, labels, class_weights,
+                                              false, scale, n_pixels, loss, static_cast<uint16_t *>(dlogits), partials,
+                                              static_cast<hipStream_t>(hip_stream)));
+}
+
 dl_status weighted_pixel_ce_map_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,
                                         const float *weight_map, float scale, int64_t n_pixels, float *loss,
                                         void *dlogits, void *workspace, size_t workspace_bytes, void *hip_stream)

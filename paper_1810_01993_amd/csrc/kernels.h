@@ -238,6 +238,7 @@ struct LogitsCeArgs {
 int logits_ce_blocks(int64_t n_pixels, int C);
 hipError_t launch_logits_ce(const LogitsCeArgs &a, bool is_bf16, hipStream_t stream);
 // loss[0] = scale * (sum of the partials, in a fixed order)
+hipError_t ce_static_partials(float **ptr);      // library-owned partial sums (per device) for the call without a workspace
 hipError_t launch_ce_finish(const float *partials, int n_partials, float scale, float *loss, hipStream_t stream);
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
                               bool per_pixel, float scale, int64_t n_pixels, float *loss, uint16_t *dlogits,

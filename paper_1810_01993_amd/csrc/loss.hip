@@ -14,6 +14,7 @@
 // fp32 partial and a one-workgroup second kernel adds the partials in a fixed
 // order, so the result is deterministic.
 #include <cstdlib>
+#include <mutex>
 
 #include "device_common.h"
 #include "kernels.h"
@@ -22,6 +23,34 @@ namespace dlk {
 
 constexpr int CE_THREADS = 256;
 constexpr int CE_MAX_BLOCKS = 1024;
+
+// The per-workgroup partial sums of the entry point that takes no workspace: one slot per workgroup
+// of the largest launch.  Every GPU the library runs on holds its own copy until the process ends.
+static __device__ __align__(256) float scratch[CE_MAX_BLOCKS];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle for the runtime, never an address a kernel may be given: the address is looked up once per
+// device, with that device current, and kept.
+hipError_t ce_static_partials(float **ptr)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static float *resolved[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!resolved[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        resolved[dev] = static_cast<float *>(p);
+    }
+    *ptr = resolved[dev];
+    return hipSuccess;
+}
 
 int ce_num_blocks(int64_t n_pixels)
 {

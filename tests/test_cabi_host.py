@@ -76,6 +76,9 @@ def test_pointer_checks_happen_before_any_launch(api):
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, -1, 16, 16, 16, 64, None) == 2
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 16, None, 0, None) == 5
     assert lib.weighted_pixel_ce_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 24, 16, 64, None) == 4
+    # the entry point without a workspace: same checks, plus its size limit, all before the first HIP call
+    assert lib.weighted_pixel_ce_fwd_bwd_static(16, 0, 16, 16, 1.0, api.CE_STATIC_MAX_PIXELS + 1, 16, 16, None) == 2
+    assert lib.weighted_pixel_ce_fwd_bwd_static(16, 0, 16, 16, 1.0, 8, None, 16, None) == 1
     assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, None, 1.0, 8, 16, 16, 16, 64, None) == 1   # no weight map
     assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, 24, 1.0, 8, 16, 16, 16, 64, None) == 4     # map misaligned
     assert lib.weighted_pixel_ce_map_fwd_bwd(16, 0, 16, 16, 1.0, 8, 16, 16, None, 0, None) == 5
