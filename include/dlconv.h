@@ -198,7 +198,9 @@ dl_status dl_ce_workspace_bytes(int64_t n_pixels, size_t *bytes);
  *   loss = scale * sum_i class_weights[label_i] * l_i
  *   dlogits_i[c] = scale * class_weights[label_i] * (softmax(z_i)[c] - [c == label_i])
  * logits, dlogits: [n_pixels, 3] in `dtype` (F16 | BF16); labels: [n_pixels]
- * uint8 in {0,1,2} (other values: undefined result, no fault); class_weights:
+ * uint8 in {0,1,2} (a pixel with any other value has weight 0: it adds nothing to
+ * the loss and its gradient is zero; also in the weight-map and the fused
+ * variants below); class_weights:
  * device float[3]; loss: device float[1].  Math is fp32 with the row maximum
  * subtracted.  n_pixels == 0 writes loss = 0. */
 dl_status weighted_pixel_ce_fwd_bwd(const void *logits, int32_t dtype, const uint8_t *labels,

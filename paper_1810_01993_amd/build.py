@@ -17,7 +17,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    # DLCONV_BUILD_TUNING=1 at BUILD time compiles the sweep knobs in (kernel sweeps only; the
+    # library as shipped reads no environment variable at run time)
+    extra = ["-DDLCONV_TUNING"] if os.environ.get("DLCONV_BUILD_TUNING") == "1" else []
+    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

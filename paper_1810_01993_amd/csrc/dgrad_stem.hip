@@ -141,10 +141,7 @@ __global__ __launch_bounds__(512) void dgrad_stem_kernel(const DgradStemArgs p)
 
 bool dgrad_stem_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_DGRAD_STEM");    // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_DGRAD_STEM", 1); // tuning override: 0 = never
     (void)N;
     return mode && R == DS_R && S == DS_R && sh == 2 && sw == 2 && ph == DS_PAD && pw == DS_PAD && dh == 1 && dw == 1 &&
            (C == 8 || C == 16) && K % 8 == 0 && K <= DS_MAXCH * BK && H >= 2 && W >= 2;

@@ -125,19 +125,13 @@ __global__ __launch_bounds__(256) void igemm_scalar_kernel(const IgemmArgs p)
 // vector-path launch (used by the tile sweeps; unset in normal use).
 static int forced_cfg()
 {
-    static int v = [] {
-        const char *e = std::getenv("DLCONV_IGEMM_CFG");
-        return e ? std::atoi(e) : -1;
-    }();
+    static const int v = tuning_knob("DLCONV_IGEMM_CFG", -1);
     return v;
 }
 
 static bool choose_c_outer(const IgemmArgs &a)
 {
-    static const int force_order = [] {
-        const char *e = std::getenv("DLCONV_C_OUTER");
-        return e ? std::atoi(e) : -1;
-    }();
+    static const int force_order = tuning_knob("DLCONV_C_OUTER", -1);
     // channel-major order needs the tap mask to fit 64 bits and no chunk that is mostly padding
     const bool cm_ok = a.TR * a.TS <= 64;
     return cm_ok && (force_order >= 0 ? force_order != 0 : (a.Cin % 32 == 0 || a.Cin >= 128));
@@ -152,10 +146,7 @@ static bool choose_c_outer(const IgemmArgs &a)
 // and the chunks per range.
 static int choose_ksplits(const IgemmArgs &a, int *chunks_per_split)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_KSPLIT");         // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_KSPLIT", 1); // tuning override: 0 = never
     *chunks_per_split = 0;
     if (!mode || forced_cfg() >= 0 || a.Cin % 8 != 0 || !choose_c_outer(a)) return 1;
     const bool dense = a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW && a.ldd == a.Nout;
@@ -193,10 +184,7 @@ static int choose_cfg(const IgemmArgs &a)
     auto blocks = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((a.Nout + bn - 1) / bn); };
     if (nmax <= 32 || a.Nout <= 32) return 104;                     // 64 x 32
     if (nmax >= 256 && blocks(256, 256) >= 200) return 100;         // 256 x 256
-    static const int min128 = [] {
-        const char *e = std::getenv("DLCONV_CFG128_MIN");   // tuning override: fewest 128 x 128 tiles that configuration is used for
-        return e ? std::atoi(e) : 200;
-    }();
+    static const int min128 = tuning_knob("DLCONV_CFG128_MIN", 200); // tuning override: fewest 128 x 128 tiles that configuration is used for
     if (nmax >= 128 && blocks(128, 128) >= min128) return 102;      // 128 x 128
     if (blocks(128, 64) >= 200) return 103;                         // 128 x 64
     return 108;                                                     // 64 x 64
@@ -204,10 +192,7 @@ static int choose_cfg(const IgemmArgs &a)
 
 bool igemm_accepts_transposed_b(const IgemmArgs &a)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_BT");             // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_BT", 1); // tuning override: 0 = never
     return mode && a.Cin % 8 == 0 && a.Nout % 8 == 0 && a.Nout >= 32 && !(forced_cfg() < 0 && thin_rows_applicable(a)) && choose_cfg(a) >= 100 &&
            choose_c_outer(a);
 }
@@ -264,10 +249,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 
 int igemm_batch_cfg(const IgemmArgs *a, int n)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_BATCH");          // tuning override: 0 = one launch per GEMM
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_BATCH", 1); // tuning override: 0 = one launch per GEMM
     if (!mode || n < 2 || n > IgemmBatch::MAX || forced_cfg() >= 0) return -1;
     // Sharing a launch pays where the single launches are short (start-up and drain of a 10 us
     // kernel, four times over); long GEMMs run better one after the other (the 3x3 stride-2

@@ -252,10 +252,7 @@ static int halo_pieces_per_wave(const IgemmArgs &a)
 
 static int halo_mode()
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_HALO");       // tuning override: 0 = never, 2 = general kernel only
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_HALO", 1); // tuning override: 0 = never, 2 = general kernel only
     return mode;
 }
 

@@ -414,10 +414,7 @@ size_t igemm_narrow5x5_split_bytes(const IgemmArgs &a)
 // output columns: not this kernel's shape).
 bool igemm_narrow5x5_applicable(const IgemmArgs &a)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_NARROW");       // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_NARROW", 1); // tuning override: 0 = never
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && a.dth == 1 && a.dtw == 1 && a.Cin % 8 == 0 &&
            a.Nout % 8 == 0 && a.Nout >= 8 && a.Nout <= N5_BN && a.ldd % 8 == 0 && !a.resid &&
@@ -427,10 +424,7 @@ bool igemm_narrow5x5_applicable(const IgemmArgs &a)
 // At most 32 input channels (one chunk), any number (a multiple of 4) of output columns, taps forward or mirrored.
 bool igemm_wide5x5_applicable(const IgemmArgs &a)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_WIDE5X5");      // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_WIDE5X5", 1); // tuning override: 0 = never
     const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW;
     return mode && dense && a.TR == N5_T && a.TS == N5_T && abs(a.dth) == 1 && abs(a.dtw) == 1 && a.Cin % 8 == 0 &&
            a.Cin <= BK && a.Nout % 4 == 0 && a.Nout > N5_BN && a.ldd % 4 == 0 && !a.resid &&

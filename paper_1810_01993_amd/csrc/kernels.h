@@ -4,7 +4,24 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#ifdef DLCONV_TUNING
+#include <cstdlib>
+#endif
+
 namespace dlk {
+
+// Sweep knobs.  The library as shipped has none: which kernel runs, with which tiles and in which
+// summation order, depends on the arguments of the call alone and never on the caller's
+// environment.  Only a build made with -DDLCONV_TUNING (kernel sweeps) reads the named variable.
+#ifdef DLCONV_TUNING
+inline int tuning_knob(const char *name, int dflt)
+{
+    const char *e = std::getenv(name);
+    return e ? std::atoi(e) : dflt;
+}
+#else
+constexpr int tuning_knob(const char *, int dflt) { return dflt; }
+#endif
 
 // Implicit-GEMM convolution engine: D[m, j] = sum_{t, c} A[pixel(m, t), c] * B[j, t, c].
 //   m indexes (n, oh, ow) of an output grid [N, OH, OW]; t = (jr, js) a grid of

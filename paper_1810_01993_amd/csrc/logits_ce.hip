@@ -132,7 +132,7 @@ __global__ __launch_bounds__(LC_THREADS, 3) void logits_ce_kernel(const LogitsCe
         // One pixel's logits -> loss term and dz (the arithmetic of the loss kernel), copies on request.
         struct Dz { float d0, d1, d2, loss; };
         auto pixel = [](float z0, float z1, float z2, int lab, float w0, float w1, float w2, float scale) __attribute__((always_inline)) {
-            const float wl = lab == 0 ? w0 : (lab == 1 ? w1 : w2);
+            const float wl = lab == 0 ? w0 : (lab == 1 ? w1 : (lab == 2 ? w2 : 0.f));   // labels outside {0,1,2}: weight 0
             const float m = fmaxf(z0, fmaxf(z1, z2));
             const float e0 = __expf(z0 - m), e1 = __expf(z1 - m), e2 = __expf(z2 - m);
             const float se = e0 + e1 + e2;

@@ -13,7 +13,7 @@
 // shuffles and across the workgroup through LDS; each workgroup writes one
 // fp32 partial and a one-workgroup second kernel adds the partials in a fixed
 // order, so the result is deterministic.
-#include <cstdlib>
+#include <algorithm>
 #include <mutex>
 
 #include "device_common.h"
@@ -54,10 +54,7 @@ hipError_t ce_static_partials(float **ptr)
 
 int ce_num_blocks(int64_t n_pixels)
 {
-    static const int max_blocks = [] {
-        const char *e = std::getenv("DLCONV_CE_BLOCKS");     // tuning override
-        return e && std::atoi(e) > 0 ? std::atoi(e) : CE_MAX_BLOCKS;
-    }();
+    static const int max_blocks = std::min(std::max(tuning_knob("DLCONV_CE_BLOCKS", CE_MAX_BLOCKS), 1), CE_MAX_BLOCKS);
     const int64_t groups = (n_pixels + 7) / 8;
     int64_t b = (groups + CE_THREADS - 1) / CE_THREADS;
     if (b > max_blocks) b = max_blocks;
@@ -66,8 +63,10 @@ int ce_num_blocks(int64_t n_pixels)
 }
 
 // One pixel: returns w * (logsumexp - z_label) and overwrites z0..z2 with the gradient.
+// A label outside {0, 1, 2} (a corrupted mask) counts as weight 0: no loss, zero gradient.
 __device__ __forceinline__ float ce_pixel(float &z0, float &z1, float &z2, int lab, float w, float scale)
 {
+    w = lab > 2 ? 0.f : w;
     const float m = fmaxf(z0, fmaxf(z1, z2));
     const float e0 = __expf(z0 - m), e1 = __expf(z1 - m), e2 = __expf(z2 - m);
     const float se = e0 + e1 + e2;

@@ -369,10 +369,7 @@ hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64
     if (n <= 0) return hipSuccess;
     if (ncols < 1 || (resid && out_dtype == 2)) return hipErrorInvalidValue;
     if (splits >= 128 && n <= 8192) return launch_reduce_g<32>(partial, splits, n, out, out_dtype, bias, relu, ncols, resid, stream);
-    static const int vec = [] {
-        const char *e = std::getenv("DLCONV_REDUCE4");        // tuning override: 0 = one output per thread always
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int vec = tuning_knob("DLCONV_REDUCE4", 1); // tuning override: 0 = one output per thread always
     const bool aligned = (reinterpret_cast<uintptr_t>(partial) % 16 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(resid) % 8 == 0);
     if (vec && n % 4 == 0 && n >= 65536 && aligned)

@@ -237,10 +237,7 @@ __global__ __launch_bounds__(512) void wgrad3x3_kernel(const WgradStripArgs p)
 
 bool wgrad3x3_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_WGRAD3X3");      // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_WGRAD3X3", 1); // tuning override: 0 = never
     return mode && R == 3 && S == 3 && sh == 1 && sw == 1 && ph == 1 && pw == 1 && dh == 1 && dw == 1 && C % 8 == 0 &&
            K % 8 == 0 && (int64_t)N * H * W >= 300000 && W >= 64 && H >= 16;
 }

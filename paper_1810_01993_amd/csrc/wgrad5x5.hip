@@ -199,10 +199,7 @@ __global__ __launch_bounds__(320) void wgrad5x5_kernel(const WgradStripArgs p)
 
 bool wgrad5x5_applicable(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int dh, int dw)
 {
-    static const int mode = [] {
-        const char *e = std::getenv("DLCONV_WGRAD5X5");      // tuning override: 0 = never
-        return e ? std::atoi(e) : 1;
-    }();
+    static const int mode = tuning_knob("DLCONV_WGRAD5X5", 1); // tuning override: 0 = never
     return mode && R == 5 && S == 5 && sh == 1 && sw == 1 && ph == 2 && pw == 2 && dh == 1 && dw == 1 && C % 8 == 0 &&
            K % 8 == 0 && K <= 32 && (int64_t)N * H * W >= 20000 && W >= 32 && H >= 16;
 }

@@ -234,10 +234,7 @@ static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
 
 WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
 {
-    static const int forced = [] {
-        const char *e = std::getenv("DLCONV_WGRAD_CFG");      // tuning override, unset in normal use
-        return e ? std::atoi(e) : -2;
-    }();
+    static const int forced = tuning_knob("DLCONV_WGRAD_CFG", -2); // tuning override, unset in normal use
     WgradPlan pl{-1, 1, 32, 0};
     if (thin_ok && forced != -1) {
         // streaming kernel: one workgroup per slice of pixels, about eight slices per CU
@@ -272,10 +269,7 @@ WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)
     // back once per slice.  The constants are fitted to measured times on MI355X.
     struct Shape { int bm, bn, per_cu; double us_per_step; };
     static const Shape shapes[4] = {{256, 256, 1, 0.92}, {128, 128, 2, 0.55}, {64, 256, 2, 0.71}, {128, 256, 1, 0.88}};
-    static const int forced_target = [] {
-        const char *e = std::getenv("DLCONV_WGRAD_TARGET");   // tuning override: workgroups wanted, unset in normal use
-        return e ? std::atoi(e) : 0;
-    }();
+    static const int forced_target = tuning_knob("DLCONV_WGRAD_TARGET", 0); // tuning override: workgroups wanted, unset in normal use
     const double outputs = (double)K * RSC;
     double best = 1e300;
     for (int cfg = 0; cfg < 4; ++cfg) {

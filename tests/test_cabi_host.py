@@ -101,3 +101,46 @@ def test_pointer_checks_happen_before_any_launch(api):
     assert lib.larc_sgd_step(tp, 1, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, 16, 8, None) == 5
     assert lib.larc_sgd_step(None, 0, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, None, 0, None) == 0     # nothing to do
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)
+
+
+_DISPATCH_PROBE = r"""
+import sys
+sys.path.insert(0, %r)
+from paper_1810_01993_amd import api
+out = []
+shapes = [(2, 768, 1152, 256, 256, 3, 1, 1, 1),     # decoder 3x3: halo-tile kernel, fused-tap filter gradient
+          (2, 48, 72, 2048, 256, 3, 1, 6, 6),       # ASPP 3x3: split reduction
+          (2, 48, 72, 1024, 256, 1, 1, 0, 1),       # 1x1
+          (2, 192, 288, 128, 128, 3, 2, 1, 1),      # stride 2: parity classes in one launch
+          (2, 768, 1152, 16, 64, 7, 2, 3, 1),       # stem
+          (2, 768, 1152, 208, 32, 5, 1, 2, 1)]      # 5x5 with 32 output channels
+for (N, H, W, C, K, R, st, pad, dil) in shapes:
+    d = api.ConvDesc(N, H, W, C, K, R, R, st, st, pad, pad, dil, dil, api.DL_F16)
+    out.append([api.dl_conv_workspace_bytes(d, p) for p in (0, 1, 2)])
+out.append(api.dl_ce_workspace_bytes(2 * 768 * 1152))
+print(out)
+"""
+
+
+def test_dispatch_does_not_read_the_environment(api):
+    """The library has no run-time knobs: the sweep variables of the tuning build change nothing (the
+    workspace sizes follow the kernel choice, the split of reductions and the slice plans), no source
+    file calls getenv outside the tuning build's helper, and the built library does not import it."""
+    import subprocess
+    import sys
+    knobs = {"DLCONV_HALO": "0", "DLCONV_KSPLIT": "0", "DLCONV_WGRAD_CFG": "1", "DLCONV_WGRAD3X3": "0",
+             "DLCONV_WGRAD5X5": "0", "DLCONV_NARROW": "0", "DLCONV_WIDE5X5": "0", "DLCONV_DGRAD_STEM": "0",
+             "DLCONV_IGEMM_CFG": "103", "DLCONV_BATCH": "0", "DLCONV_BT": "0", "DLCONV_CE_BLOCKS": "7",
+             "DLCONV_WGRAD_TARGET": "64", "DLCONV_C_OUTER": "0", "DLCONV_CFG128_MIN": "1", "DLCONV_REDUCE4": "0"}
+    clean = {k: v for k, v in os.environ.items() if not k.startswith("DLCONV_")}
+    code = _DISPATCH_PROBE % ROOT
+    plain = subprocess.run([sys.executable, "-c", code], env=clean, capture_output=True, text=True, check=True).stdout
+    steered = subprocess.run([sys.executable, "-c", code], env={**clean, **knobs}, capture_output=True, text=True,
+                             check=True).stdout
+    assert plain == steered and plain.strip().startswith("[[")
+    csrc = os.path.join(ROOT, "paper_1810_01993_amd", "csrc")
+    for name in os.listdir(csrc):
+        if name.endswith(".hip"):
+            assert "getenv" not in open(os.path.join(csrc, name)).read(), name
+    syms = subprocess.run(["nm", "-D", "--undefined-only", api.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    assert "getenv" not in syms

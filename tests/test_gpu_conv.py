@@ -28,46 +28,69 @@ def _say(msg):
     sys.stdout.flush()
 
 
-def check_layer(api, layer: ConvLayer, dtype: str, seed: int, x_kind="half_normal", n_samples=4096,
-                dw_f32=False, passes=("fwd", "dgrad", "wgrad")):
-    """Run the requested passes on the GPU and compare with the oracle.
-    Returns {pass: rel_err}."""
+def check_layer(api, layer: ConvLayer, dtype: str, seed: int, x_kind="half_normal", n_samples=8192,
+                dw_f32=False, passes=("fwd", "dgrad", "wgrad"), full_passes=(), dw_per_cell=0):
+    """Run the requested passes on the GPU and compare with the oracle: on the whole tensor where the
+    oracle's cost allows (U.FULL_LIMIT; always for the passes named in `full_passes`), otherwise on
+    n_samples uniformly drawn outputs plus every element of the first and last two rows and columns
+    (activations) or, with dw_per_cell > 0, that many elements of every 32 x 32-channel block of every
+    tap (filter gradient).  Every output and every workspace lies between marked guard zones, which
+    must survive the call.  Returns {pass: rel_err}."""
     (x32, xb), (w32, wb), (dy32, dyb) = U.conv_inputs(layer, dtype, seed, x_kind)
     desc = api.desc_from_layer(layer, dtype, dw_f32=dw_f32)
     s = U.shape_of(layer)
-    full = layer.flops() <= U.FULL_ORACLE_FLOPS
     xd, wd, dyd = U.to_device(xb, dtype), U.to_device(wb, dtype), U.to_device(dyb, dtype)
+    tdt = U.TORCH_DTYPE[dtype]
     errs = {}
     for which in passes:
+        full = which in full_passes or layer.flops() <= U.FULL_LIMIT[which]
         _say(f"[case] {layer.name} {dtype} {which} N{layer.N} {layer.H}x{layer.W}x{layer.C}->{layer.K} "
              f"{layer.R}x{layer.S} s{layer.stride} p{layer.pad} d{layer.dil} seed={seed} full={full}")
+        pass_id = {"fwd": api.PASS_FWD, "dgrad": api.PASS_BWD_DATA, "wgrad": api.PASS_BWD_FILTER}[which]
+        ws_bytes = api.dl_conv_workspace_bytes(desc, pass_id)
+        ws_buf, ws = U.guarded_workspace(ws_bytes)
         if which == "fwd":
-            got = U.to_host_f64(api.conv2d_fwd(desc, xd, wd))
+            out_buf, out = U.guarded((layer.N, layer.P, layer.Q, layer.K), tdt)
+            api.conv2d_fwd(desc, xd, wd, y=out, workspace=ws)
+        elif which == "dgrad":
+            out_buf, out = U.guarded((layer.N, layer.H, layer.W, layer.C), tdt)
+            api.conv2d_bwd_data(desc, dyd, wd, dx=out, workspace=ws)
+        else:
+            out_buf, out = U.guarded((layer.K, layer.R, layer.S, layer.C), torch.float32 if dw_f32 else tdt)
+            api.conv2d_bwd_filter(desc, xd, dyd, dw=out, workspace=ws)
+        torch.cuda.synchronize()
+        assert U.guards_intact(out_buf), f"{layer.name} {which}: write outside the output tensor"
+        assert U.workspace_guards_intact(ws_buf, ws_bytes), f"{layer.name} {which}: write outside the workspace"
+        got = U.to_host_f64(out)
+        del out, out_buf, ws, ws_buf
+        if which == "fwd":
             if full:
                 ref = oracle.conv_fwd(s, x32, w32)
             else:
-                idx = np.union1d(U.sample_indices(got.shape, n_samples, seed), U.border_indices(got.shape, 256, seed))
+                idx = np.union1d(U.sample_indices(got.shape, n_samples, seed), U.all_border_indices(got.shape, seed))
                 ref = oracle.conv_fwd_at(s, x32, w32, idx)
                 got = got.ravel()[idx]
         elif which == "dgrad":
-            got = U.to_host_f64(api.conv2d_bwd_data(desc, dyd, wd))
             if full:
                 ref = oracle.conv_bwd_data(s, dy32, w32)
             else:
-                idx = np.union1d(U.sample_indices(got.shape, n_samples, seed), U.border_indices(got.shape, 256, seed))
+                idx = np.union1d(U.sample_indices(got.shape, n_samples, seed), U.all_border_indices(got.shape, seed))
                 ref = oracle.conv_bwd_data_at(s, dy32, w32, idx)
                 got = got.ravel()[idx]
         else:
-            got = U.to_host_f64(api.conv2d_bwd_filter(desc, xd, dyd))
             if full:
                 ref = oracle.conv_bwd_filter(s, x32, dy32)
             else:
                 npix = layer.N * layer.P * layer.Q
-                idx = U.sample_indices(got.shape, max(16, min(n_samples, int(4e9 // npix))), seed)
+                if dw_per_cell > 0:
+                    idx = U.stratified_filter_indices(got.shape, dw_per_cell, seed)
+                else:
+                    idx = U.sample_indices(got.shape, max(16, min(n_samples, int(4e9 // npix))), seed)
                 ref = oracle.conv_bwd_filter_at(s, x32, dy32, idx)
                 got = got.ravel()[idx]
-        torch.cuda.synchronize()
         assert np.all(np.isfinite(got)), f"{layer.name} {which}: non-finite output"
+        if dtype == "f16" and ref.size:
+            assert float(np.max(np.abs(ref))) < U.FP16_MAX_REF, f"{layer.name} {which}: the exact result leaves fp16's range"
         errs[which] = U.rel_err(got, ref)
         tol = U.TOL[dtype]
         assert errs[which] <= tol, f"{layer.name} {dtype} {which}: max|err|/max|ref| = {errs[which]:.3e} > {tol}"
@@ -146,7 +169,7 @@ def test_random_shapes(api, layer, dtype):
 
 
 def test_big_tile_path(api):
-    # enough 256-row tiles that the wide configuration is selected; full oracle
+    # enough 256-row tiles that the wide configuration is selected (8.2 GFLOP: whole tensors)
     check_layer(api, L("bigtile", 2, 192, 288, 16, 256, 3, 3, 1, 1, 1), "f16", synth.seed_for(0, 501))
 
 
@@ -261,22 +284,59 @@ def test_config4_aspp(api, i):
 _, CFG5 = layers.config5()
 
 
+FULL_RES = ("dec.3x3.304-256", "dec.3x3.256-256", "logits.256-3")       # 87 % of the step's FLOPs
+
+
 @pytest.mark.parametrize("layer", CFG5, ids=[l.name for l in CFG5])
 def test_config5_full_size_layers(api, layer):
-    """Every distinct layer shape of the network at its real size, fp16."""
+    """Every distinct layer shape of the network at its real size, fp16.  Whole tensors wherever the
+    oracle's cost allows; the three full-resolution layers: 65536 uniformly drawn outputs plus every
+    element of the first and last two rows and columns (forward, data gradient), and the filter
+    gradient in full (1.1-1.2 T multiply-adds in the oracle, about a minute each)."""
     kind = "fields" if layer.name == "stem7x7" else "half_normal"
-    big = layer.H * layer.W * layer.N * max(layer.C, layer.K) > 2e8
+    big = layer.name in FULL_RES
     check_layer(api, layer, "f16", synth.seed_for(5, 10 * CFG5.index(layer)), x_kind=kind,
-                n_samples=16384 if big else 4096)
+                n_samples=65536 if big else 16384, full_passes=("wgrad",) if big else ())
     torch.cuda.empty_cache()
 
 
 def test_decoder_layer_bf16_full_size(api):
-    """The dominant layer at its benchmark size in bfloat16: 3x3 halo kernel (forward, data gradient) and the
-    fused-tap filter-gradient kernel, sampled outputs."""
+    """The dominant layer at its benchmark size in bfloat16: 3x3 halo kernel (forward, data gradient) on
+    65536 outputs plus all border elements, the fused-tap filter-gradient kernel on 8 elements of every
+    (32 output channels, tap, 32 input channels) block."""
     layer = [l for l in CFG5 if l.name == "dec.3x3.256-256"][0]
-    check_layer(api, layer, "bf16", synth.seed_for(5, 777), n_samples=16384)
+    check_layer(api, layer, "bf16", synth.seed_for(5, 777), n_samples=65536, dw_per_cell=8)
     torch.cuda.empty_cache()
+
+
+# Whole-tensor comparisons for the two kernels that carry the decoder: cases small enough for the full
+# oracle that still meet the kernels' selection rules (3x3 halo-tile kernel: >= 200 tiles; fused-tap
+# filter gradient: >= 300 000 pixels).  Each column-tile width of the halo kernel (128, 160, <= 64
+# channels) is reached from the forward pass (K) and from the data gradient (C); several channel chunks
+# with a ragged last one; ragged patches on both image axes; both dtypes.
+DOMINANT = [
+    (L("full.halo3x3.k128", 2, 160, 320, 8, 128, 3, 3, 1, 1, 1), "f16", ("fwd", "dgrad")),
+    (L("full.halo3x3.k160", 2, 160, 320, 8, 160, 3, 3, 1, 1, 1), "bf16", ("fwd", "dgrad")),
+    (L("full.halo3x3.k64", 2, 160, 320, 8, 64, 3, 3, 1, 1, 1), "f16", ("fwd", "dgrad")),
+    (L("full.halo3x3.c128", 2, 160, 320, 128, 8, 3, 3, 1, 1, 1), "bf16", ("fwd", "dgrad")),
+    (L("full.halo3x3.c160", 2, 160, 320, 160, 8, 3, 3, 1, 1, 1), "f16", ("fwd", "dgrad")),
+    (L("full.halo3x3.c64", 2, 160, 320, 64, 8, 3, 3, 1, 1, 1), "bf16", ("fwd", "dgrad")),
+    (L("full.halo3x3.chunks.c72k128", 1, 170, 630, 72, 128, 3, 3, 1, 1, 1), "f16", ("fwd",)),
+    (L("full.halo3x3.chunks.c128k72", 1, 170, 630, 128, 72, 3, 3, 1, 1, 1), "f16", ("dgrad",)),
+    (L("full.halo3x3.k304.c40", 1, 165, 650, 40, 304, 3, 3, 1, 1, 1), "bf16", ("fwd",)),
+    (L("full.halo3x3.c304.k16", 1, 165, 650, 304, 16, 3, 3, 1, 1, 1), "f16", ("dgrad",)),
+    (L("full.wgrad3x3.c8k16", 1, 512, 608, 8, 16, 3, 3, 1, 1, 1), "f16", ("wgrad",)),
+    (L("full.wgrad3x3.c40k72", 1, 515, 611, 40, 72, 3, 3, 1, 1, 1), "bf16", ("wgrad",)),
+    (L("full.wgrad3x3.c304k256", 1, 400, 768, 304, 256, 3, 3, 1, 1, 1), "f16", ("wgrad",)),
+]
+
+
+@pytest.mark.parametrize("layer,dtype,passes", DOMINANT, ids=[l.name for l, _, _ in DOMINANT])
+def test_dominant_kernels_whole_tensors(api, layer, dtype, passes):
+    for which in passes:                       # keeps the oracle's share of the run to seconds per case
+        assert layer.flops() <= {"fwd": 100e9, "dgrad": 25e9, "wgrad": 500e9}[which], (layer.name, which)
+    check_layer(api, layer, dtype, synth.seed_for(0, 800 + [l.name for l, _, _ in DOMINANT].index(layer.name)),
+                x_kind="normal", passes=passes, full_passes=passes)
 
 
 def test_determinism_of_the_large_layer_kernels(api):

@@ -135,3 +135,32 @@ def test_argument_errors(api):
         api.logits_ce_fused_fwd_bwd(x, w, lab, cw, 1.0)
     with pytest.raises(ValueError):
         api.logits_ce_fused_fwd_bwd(torch.zeros((10, 64), dtype=torch.float16, device="cuda"), w, lab, cw, 1.0)
+
+
+def test_labels_outside_the_classes_have_weight_zero(api):
+    """Pixels with a label other than 0, 1, 2 drop out: zero dlogits and dx rows, and loss and dW are
+    those of the remaining pixels alone (the oracle on the good pixels with the same scale)."""
+    for n, C, dtype in ((5000, 256, "f16"), (3001, 304, "bf16")):
+        seed = synth.seed_for(7, 60 + C)
+        print(f"[case] logits_ce_fused bad labels n={n} C={C} {dtype}", flush=True)
+        x32, xb, w32, wb, labels = _inputs(n, C, dtype, seed)
+        bad = np.zeros(n, dtype=bool)
+        bad[synth.rng(seed + 9).integers(0, n, n // 20)] = True
+        bad[[0, n - 1]] = True
+        labels_bad = labels.copy()
+        labels_bad[bad] = 200
+        cw = np.asarray(synth.CLASS_WEIGHTS, dtype=np.float32)
+        scale = 1.0 / 64
+        _, loss, dlogits, dx, dw = api.logits_ce_fused_fwd_bwd(
+            U.to_device(xb, dtype), U.to_device(wb, dtype), torch.from_numpy(labels_bad).cuda(),
+            torch.from_numpy(cw).cuda(), scale)
+        torch.cuda.synchronize()
+        good = ~bad
+        _, rloss, rdz, rdx, rdw = logits_ce_fused(x32[good], w32, labels[good], cw.astype(np.float64),
+                                                  float(np.float32(scale)))
+        gdz, gdx = U.to_host_f64(dlogits), U.to_host_f64(dx)
+        assert np.all(gdz[bad] == 0.0) and np.all(gdx[bad] == 0.0)
+        assert U.rel_err(gdz[good], rdz) <= U.TOL[dtype]
+        assert U.rel_err(gdx[good], rdx) <= U.TOL[dtype]
+        assert abs(float(loss.item()) - rloss) <= LOSS_RTOL * abs(rloss)
+        assert U.rel_err(dw.double().cpu().numpy().reshape(3, C), rdw) <= DW_TOL[dtype]

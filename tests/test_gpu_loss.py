@@ -136,3 +136,36 @@ def test_weight_map_sizes_and_ragged_tails(api, n, dtype):
 def test_weight_map_full_mask_and_class_table_equivalence(api):
     _run_map(api, 2 * 768 * 1152, "f16", synth.seed_for(5, 995), from_table=True)
     _run_map(api, 2 * 1024 * 4 * 512 + 8 * 70 + 3, "bf16", synth.seed_for(0, 996))
+
+
+def test_labels_outside_the_classes_have_weight_zero(api):
+    """A corrupted mask (label 3 or 255) must not train silently on class 2: such pixels add
+    nothing to the loss and get a zero gradient, in whole-wavefront trips, in the left-over groups
+    of 8 and in the ragged tail, with the class table and with the weight map."""
+    n = 2 * 1024 * 4 * 512 + 8 * 70 + 5
+    seed = synth.seed_for(0, 980)
+    for dtype in ("f16", "bf16"):
+        print(f"[case] weighted_ce bad labels n={n} {dtype}", flush=True)
+        z32, zb = synth.quantize(synth.normal(seed, (n, 3)), dtype)
+        labels = synth.rng(seed + 1).choice(3, size=n, p=synth.CLASS_FREQ).astype(np.uint8)
+        bad = np.zeros(n, dtype=bool)
+        bad[synth.rng(seed + 2).integers(0, n, 5000)] = True
+        bad[[0, 511, 512, n - 600, n - 9, n - 5, n - 1]] = True      # first trip, trip boundary, groups of 8, tail
+        labels_bad = labels.copy()
+        labels_bad[bad] = np.where(np.arange(n)[bad] % 2 == 0, 3, 255).astype(np.uint8)
+        cw = np.asarray(synth.CLASS_WEIGHTS, dtype=np.float32)
+        scale = 2.0 ** -10
+        wm = cw[labels].astype(np.float32)
+        wm[bad] = 0.0
+        ref_loss, ref_dz = oracle.weighted_ce_map(z32, labels, wm.astype(np.float64), float(np.float32(scale)))
+        zd, ld = U.to_device(zb, dtype), torch.from_numpy(labels_bad).cuda()
+        for which in ("table", "map"):
+            if which == "table":
+                loss, dz = api.weighted_pixel_ce_fwd_bwd(zd, ld, torch.from_numpy(cw).cuda(), scale)
+            else:
+                loss, dz = api.weighted_pixel_ce_map_fwd_bwd(zd, ld, torch.from_numpy(cw[labels]).cuda(), scale)
+            torch.cuda.synchronize()
+            g = U.to_host_f64(dz)
+            assert np.all(g[bad] == 0.0), which
+            assert U.rel_err(g, ref_dz) <= U.TOL[dtype], which
+            assert abs(float(loss.item()) - ref_loss) <= LOSS_RTOL * abs(ref_loss), (which, loss.item(), ref_loss)
