@@ -8,10 +8,12 @@ plus the weighted pixel cross-entropy on the full-resolution 3-class logits.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--table]
+    python bench.py --config N        (N = 1..4: per-layer table of that configuration, oracle timed beside it)
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -61,6 +63,13 @@ def parse_args():
                     help="2-4: filter gradients of the small layers run on 1-3 more HIP streams beside the "
                          "data-gradient chain")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "igemm_halo3x3_config5_traffic.txt"))
+    ap.add_argument("--config", type=int, default=5, choices=(1, 2, 3, 4, 5),
+                    help="5 (default): the headline step.  1-4: instead of the step, time every layer and pass of that "
+                         "configuration in its own dtype and the fp64 oracle on the same layer in full; prints a table "
+                         "and one JSON line per configuration")
+    ap.add_argument("--no-microbench", action="store_true",
+                    help="skip the register-resident MFMA loop and the plain streaming kernels that are run beside the "
+                         "step (the machine's ceilings on this box, printed as context in the same line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -128,7 +137,7 @@ def cpu_baseline():
             "sample": f"fwd+dgrad+wgrad of a {rows}x1152 slab (1 image) of dec.3x3.256-256, fp64, {dt:.1f} s"}
 
 
-def loss_hbm_resident(api, torch, mult=64):
+def loss_hbm_resident(api, torch, mult=64, probes=True):
     """The loss kernel on mult x the step's pixel count (1.47 GB of traffic at 64x): the step's own 23 MB
     fit the last-level caches and take two kernel launches, so bandwidth is judged on this size."""
     n = 2 * 768 * 1152 * mult
@@ -152,20 +161,84 @@ def loss_hbm_resident(api, torch, mult=64):
         ts.append(a.elapsed_time(b) / 10)
     ms = float(np.median(ts))
     gbs = 13 * n / (ms * 1e-3) / 1e9
-    return {"n_pixels": n, "ms": ms, "gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    out = {"n_pixels": n, "ms": ms, "gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    if probes:
+        # the same buffers through kernels that only move the bytes (no LDS hand-over, no arithmetic)
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        nbytes = 6 * n
+        for mode, name, moved in ((0, "read", nbytes), (1, "copy", 2 * nbytes), (2, "write", nbytes),
+                                  (3, "loss_traffic_mix", 13 * n)):
+            runp = lambda: api.probe_stream(mode, logits, labels, dl, nbytes, sink)
+            runp()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(3):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(5):
+                    runp()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) / 5)
+            out[f"probe_{name}_gbs"] = moved / (float(np.median(ts)) * 1e-3) / 1e9
+    return out
+
+
+def mfma_microbench(api, torch, iters=20000):
+    """Register-resident MFMA loops (no memory traffic) in this process, on this machine: what the matrix
+    units sustain with constant operands and with operands distributed like the benchmark's (the chip
+    is power-limited: the shader clock drops with the operands' switching activity).  Context for the
+    roofline fractions, which keep the published 2.5 PFLOP/s."""
+    sink = torch.empty(api.PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    out = {}
+    for shape, sname in ((1, "16x16x32_f16"), (0, "32x32x16_f16")):
+        for operands, oname in ((0, "constant_operands"), (1, "bench_like_operands")):
+            api.probe_mfma(shape, operands, iters // 10, sink, clocks)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            flop = api.probe_mfma(shape, operands, iters, sink, clocks)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            wall, cyc = (int(v) for v in clocks.cpu())
+            out[f"{sname}.{oname}"] = {"tflops": flop / (ms * 1e-3) / 1e12, "ms": ms,
+                                       "shader_clock_mhz": cyc / (wall / 100.0) if wall else None}
+    return out
+
+
+KERNEL_SOURCES = ("igemm_halo3x3.hip", "device_common.h")       # what the dominant kernel is compiled from
+
+
+def kernel_source_hash():
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_1810_01993_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def read_traffic(path):
-    """HBM bytes per launch of the dominant kernel, from the committed
-    rocprofv3 counter summary (a 'bytes_per_launch = <number>' line)."""
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
+    (its 'bytes_per_launch = <number>' line), and where that number comes from: the file, and whether
+    the kernel source it was measured on ('kernel_source_sha = <hash>') is the one in the tree now.
+    A stale figure is still printed, flagged."""
+    traffic, sha = None, None
     try:
         with open(path) as f:
             for line in f:
-                if line.strip().startswith("bytes_per_launch"):
-                    return float(line.split("=")[1].split()[0])
+                t = line.strip()
+                if t.startswith("bytes_per_launch"):
+                    traffic = float(t.split("=")[1].split()[0])
+                elif t.startswith("kernel_source_sha"):
+                    sha = t.split("=")[1].split()[0]
     except OSError:
         pass
-    return None
+    now = kernel_source_hash()
+    src = {"file": os.path.relpath(path, ROOT), "measured_on_kernel_source_sha": sha, "current_kernel_source_sha": now,
+           "current": sha == now}
+    return traffic, src
 
 
 def deconv_table(args):
@@ -270,6 +343,85 @@ def tiramisu_table(args):
           f"({2 / (total_ms * 1e-3):.1f} samples/s for the convolutions alone)")
 
 
+def config_table(args):
+    """Configurations 1-4 (the parity cases that are not the headline): every layer and pass in the
+    configuration's own dtype, median HIP-event time over --steps calls with rotating buffer sets
+    (so that the 1x1 layers do not re-read cache-resident tensors), and beside it the fp64 oracle
+    on the very same layer in full, on the host cores (a baseline, not a target)."""
+    import torch
+    import oracle
+    from paper_1810_01993_amd import api, layers, synth
+
+    torch.cuda.set_device(0)
+    dtype, table = {1: layers.config1, 2: layers.config2, 3: layers.config3, 4: layers.config4}[args.config]()
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float16
+    cores = len(os.sched_getaffinity(0))
+    if os.environ.get("OMP_NUM_THREADS"):
+        cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
+    print(f"# config {args.config}, {dtype}, fp32 accumulate; oracle: fp64 on {cores} host cores", flush=True)
+    print(f"{'layer':24s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s} "
+          f"{'oracle s':>9s} {'oracle GFLOP/s':>14s}  kernels", flush=True)
+    tot_ms, tot_flop, tot_orc = 0.0, 0.0, 0.0
+    for li, layer in enumerate(table):
+        seed = synth.seed_for(args.config, 10 * li)
+        kind = "fields" if layer.R == 7 else "half_normal"
+        xs = (layer.N, layer.H, layer.W, layer.C)
+        x64 = synth.smooth_fields(seed, *xs) if kind == "fields" else synth.half_normal(seed, xs)
+        w64 = synth.he_filter(seed + 1, layer.K, layer.R, layer.S, layer.C)
+        dy64 = synth.normal(seed + 2, (layer.N, layer.P, layer.Q, layer.K))
+        (x32, xb), (w32, wb), (dy32, dyb) = (synth.quantize(t, dtype) for t in (x64, w64, dy64))
+        del x64, w64, dy64
+        dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(tdt).cuda()
+        nsets = max(2, min(8, int(6e8 // max(layer.bytes_fwd(), 1))))       # > 512 MB of rotating buffers for small layers
+        sets = []
+        desc = api.desc_from_layer(layer, dtype)
+        for _ in range(nsets):
+            x, w, dy = dev(xb), dev(wb), dev(dyb)
+            sets.append((x, w, dy, torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w),
+                         torch.empty(max(16, max(api.dl_conv_workspace_bytes(desc, p) for p in range(3))),
+                                     dtype=torch.uint8, device="cuda")))
+        shp = oracle.ConvShape(layer.N, layer.H, layer.W, layer.C, layer.K, layer.R, layer.S, layer.stride, layer.pad, layer.dil)
+        calls = {"fwd": (lambda b: api.conv2d_fwd(desc, b[0], b[1], y=b[3], workspace=b[6]), api.PASS_FWD,
+                         lambda: oracle.conv_fwd(shp, x32, w32)),
+                 "dgrad": (lambda b: api.conv2d_bwd_data(desc, b[2], b[1], dx=b[4], workspace=b[6]), api.PASS_BWD_DATA,
+                           lambda: oracle.conv_bwd_data(shp, dy32, w32)),
+                 "wgrad": (lambda b: api.conv2d_bwd_filter(desc, b[0], b[2], dw=b[5], workspace=b[6]), api.PASS_BWD_FILTER,
+                           lambda: oracle.conv_bwd_filter(shp, x32, dy32))}
+        for which, (fn, pid, orc) in calls.items():
+            for i in range(max(args.warmup, nsets)):
+                fn(sets[i % nsets])
+            torch.cuda.synchronize()
+            ts = []
+            for i in range(max(args.steps, 20)):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn(sets[i % nsets])
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            ms = float(np.median(ts))
+            t0 = time.perf_counter()
+            orc()
+            osec = time.perf_counter() - t0
+            tf = layer.flops() / (ms * 1e-3) / 1e12
+            gbs = layer.bytes_fwd() / (ms * 1e-3) / 1e9
+            tot_ms += ms
+            tot_flop += layer.flops()
+            tot_orc += osec
+            print(f"{layer.name:24s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
+                  f"{100 * gbs / HBM_PEAK_GBS:6.1f} {osec:9.2f} {layer.flops() / osec / 1e9:14.1f}  "
+                  f"{api.dl_conv_describe(desc, pid)}", flush=True)
+        del sets
+        torch.cuda.empty_cache()
+    line = {"metric": f"conv fwd+bwd TFLOP/s, config {args.config} (sum over its layers and passes, one stream)",
+            "value": tot_flop / (tot_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "dtype": dtype, "data": "synthetic",
+            "config": {"workload": f"config{args.config}", "ms_sum_of_medians": tot_ms, "flop": tot_flop,
+                       "frac_of_mfma_peak": tot_flop / (tot_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
+            "cpu_baseline": {"value": tot_flop / tot_orc / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                             "sample": f"the same layers and passes in full, {tot_orc:.1f} s"}}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -287,6 +439,9 @@ def main():
         return
     if args.tiramisu_table:
         tiramisu_table(args)
+        return
+    if args.config != 5:
+        config_table(args)
         return
     _, table = layers.config5()
 
@@ -401,7 +556,8 @@ def main():
                 times.setdefault((who, which), []).append(opened[(who, which)].elapsed_time(e))
     med = {k: float(np.median(v)) for k, v in times.items()}
 
-    loss_big = loss_hbm_resident(api, torch)
+    loss_big = loss_hbm_resident(api, torch, probes=not args.no_microbench)
+    micro = None if args.no_microbench else mfma_microbench(api, torch)
 
     step_flops = layers.total_flops(table, passes=3)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
@@ -433,6 +589,17 @@ def main():
         print(f"sum of per-call medians: conv {conv_ms:.3f} ms, loss {loss_ms:.4f} ms; wall {ms_per_step:.3f} ms/step",
               file=sys.stderr)
 
+    # the dominant kernel's name comes from the dispatch these calls actually take
+    pass_id = {"fwd": api.PASS_FWD, "dgrad": api.PASS_BWD_DATA, "wgrad": api.PASS_BWD_FILTER}
+    plans = []
+    for i, st in enumerate(net):
+        for (name, which) in DOMINANT_CALLS:
+            if st.layer.name == name:
+                plans.append(f"{name} {which}: " + api.dl_conv_describe(st.desc, pass_id[which]))
+    main_kernels = sorted({k.split("[")[0] for pl in plans for k in pl.split(": ", 1)[1].split("; ")
+                           if not k.startswith("filter_block_kernel")})
+    traffic, traffic_src = read_traffic(args.traffic_file)
+
     out = {
         "metric": "conv fwd+bwd TFLOP/s, DeepLabv3+ layers @1152x768x16 (63 conv layers x fwd/dgrad/wgrad + weighted pixel CE)",
         "value": value,
@@ -451,10 +618,10 @@ def main():
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
                    "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9,
-                   "loss_hbm_resident": loss_big},
+                   "loss_hbm_resident": loss_big, "mfma_microbench": micro},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": read_traffic(args.traffic_file),
-                     "kernel": f"igemm_halo3x3_kernel<{'BF16' if args.dtype == 'bf16' else 'F16'}, 4>: fwd+dgrad of the two full-resolution decoder 3x3 layers",
+                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
+                     "kernel": " + ".join(main_kernels) + f" ({args.dtype})", "dispatch": plans,
                      "launches_per_step": dom_n,
                      "avg_launch_ms": dom_ms / dom_n, "flop_per_launch": dom_flops / dom_n},
     }

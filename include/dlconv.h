@@ -66,6 +66,14 @@ dl_status dl_conv_out_shape(const dl_conv_desc *desc, int32_t *P, int32_t *Q);
 /* Bytes of device scratch the given pass (DL_PASS_*) needs; may be 0. */
 dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *bytes);
 
+/* Which kernels the given pass of this convolution launches, in order, each with
+ * its grid, as text ("name<tile>[workgroups]; ..."), NUL-terminated and cut to
+ * buf_bytes.  The answer comes from the entry point's own dispatch code run
+ * with launches turned into log lines, so it needs no GPU, touches no device
+ * memory and cannot disagree with what a real call does.  For measurement
+ * reports and dispatch tests. */
+dl_status dl_conv_describe(const dl_conv_desc *desc, int pass, char *buf, size_t buf_bytes);
+
 /* Forward convolution, incl. atrous convolution with a dilation factor
  * (paper, Sec. "Segmentation Architecture"):
  *   y[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r*dil_h,

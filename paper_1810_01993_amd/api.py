@@ -19,11 +19,15 @@ LIB_PATH = os.path.join(_HERE, "libdlconv.so")
 DL_F16, DL_BF16, DL_F32 = 0, 1, 2
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_FILTER = 0, 1, 2
 
-EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_fwd_bias_add_relu", "conv2d_bwd_data",
+EXPORTS = ("dl_conv_out_shape", "dl_conv_workspace_bytes", "dl_conv_describe", "conv2d_fwd", "conv2d_fwd_bias_relu", "conv2d_fwd_bias_add_relu", "conv2d_bwd_data",
            "conv2d_bwd_filter", "conv2d_transpose_fwd", "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter",
            "dl_bias_relu_bwd_workspace_bytes", "bias_relu_bwd", "dl_larc_workspace_bytes", "larc_sgd_step", "dl_ce_workspace_bytes", "weighted_pixel_ce_fwd_bwd", "weighted_pixel_ce_fwd_bwd_static",
            "weighted_pixel_ce_map_fwd_bwd",
            "dl_logits_ce_workspace_bytes", "logits_ce_fused_fwd_bwd", "dl_status_string")
+
+
+PROBE_EXPORTS = ("dl_probe_mfma", "dl_probe_stream")       # include/dlprobe.h: measurement aids
+PROBE_SINK_FLOATS = 1024 * 256
 
 
 class DlError(RuntimeError):
@@ -72,6 +76,7 @@ def _load() -> ctypes.CDLL:
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     lib.dl_conv_out_shape.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
     lib.dl_conv_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.dl_conv_describe.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, sz]
     for name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_filter", "conv2d_transpose_fwd",
                  "conv2d_transpose_bwd_data", "conv2d_transpose_bwd_filter"):
         getattr(lib, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -89,7 +94,9 @@ def _load() -> ctypes.CDLL:
     lib.dl_logits_ce_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.logits_ce_fused_fwd_bwd.argtypes = [vp, vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int64, ctypes.c_int32,
                                             vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp]
-    for name in EXPORTS:
+    lib.dl_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.dl_probe_stream.argtypes = [ctypes.c_int32, vp, vp, vp, ctypes.c_int64, vp, vp]
+    for name in EXPORTS + PROBE_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     lib.dl_status_string.argtypes = [ctypes.c_int]
     lib.dl_status_string.restype = ctypes.c_char_p
@@ -134,6 +141,13 @@ def dl_conv_workspace_bytes(desc: ConvDesc, which: int) -> int:
     n = ctypes.c_size_t()
     _check(_lib.dl_conv_workspace_bytes(ctypes.byref(desc.c_struct()), which, ctypes.byref(n)), "dl_conv_workspace_bytes")
     return n.value
+
+
+def dl_conv_describe(desc: ConvDesc, which: int) -> str:
+    """The kernels (with grids) that pass ``which`` of this convolution launches, in order."""
+    buf = ctypes.create_string_buffer(2048)
+    _check(_lib.dl_conv_describe(ctypes.byref(desc.c_struct()), which, buf, len(buf)), "dl_conv_describe")
+    return buf.value.decode()
 
 
 def dl_ce_workspace_bytes(n_pixels: int) -> int:
@@ -470,6 +484,23 @@ def logits_ce_workspace_bytes(n_pixels: int, C: int) -> int:
     need = ctypes.c_size_t(0)
     _check(_lib.dl_logits_ce_workspace_bytes(n_pixels, C, ctypes.byref(need)), "dl_logits_ce_workspace_bytes")
     return int(need.value)
+
+
+def probe_mfma(shape: int, operands: int, iters: int, sink: torch.Tensor, clocks: torch.Tensor) -> float:
+    """Enqueue the register-resident MFMA loop (include/dlprobe.h); returns the FLOPs it issues.
+    sink: float32[PROBE_SINK_FLOATS], clocks: int64[2] (wall-clock ticks at 100 MHz, shader cycles)."""
+    if sink.dtype != torch.float32 or sink.numel() < PROBE_SINK_FLOATS or clocks.dtype != torch.int64 or clocks.numel() < 2:
+        raise ValueError("sink float32[PROBE_SINK_FLOATS] and clocks int64[2] required")
+    flop = ctypes.c_double(0.0)
+    _check(_lib.dl_probe_mfma(shape, operands, iters, _dev_ptr(sink), _dev_ptr(clocks), ctypes.byref(flop), _stream()),
+           "dl_probe_mfma")
+    return flop.value
+
+
+def probe_stream(mode: int, src, aux, dst, nbytes: int, sink: torch.Tensor) -> None:
+    """Enqueue one plain streaming kernel (include/dlprobe.h): 0 read, 1 copy, 2 write, 3 the loss's traffic mix."""
+    _check(_lib.dl_probe_stream(mode, _dev_ptr(src), _dev_ptr(aux), _dev_ptr(dst), nbytes, _dev_ptr(sink), _stream()),
+           "dl_probe_stream")
 
 
 def desc_from_layer(layer, dtype: str, dw_f32: bool = False) -> ConvDesc:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdlconv.so")
-SOURCES = ["api.hip", "igemm.hip", "igemm_dma.hip", "igemm_halo.hip", "igemm_halo3x3.hip", "igemm_narrow5x5.hip", "dgrad_stem.hip", "wgrad.hip", "wgrad_dma.hip", "wgrad3x3.hip", "wgrad5x5.hip", "thin.hip", "loss.hip", "logits_ce.hip", "pointwise.hip", "larc.hip"]
+SOURCES = ["api.hip", "igemm.hip", "igemm_dma.hip", "igemm_halo.hip", "igemm_halo3x3.hip", "igemm_narrow5x5.hip", "dgrad_stem.hip", "wgrad.hip", "wgrad_dma.hip", "wgrad3x3.hip", "wgrad5x5.hip", "thin.hip", "loss.hip", "logits_ce.hip", "pointwise.hip", "larc.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -7,6 +7,10 @@
 #include "../../include/dlconv.h"
 #include "kernels.h"
 
+namespace dlk {
+thread_local LaunchLog *launch_log = nullptr;
+}
+
 namespace {
 
 constexpr int64_t MAX_ELEMS = 0x7FF00000;     // 32-bit byte offsets, with room above for the out-of-range marker
@@ -506,6 +510,36 @@ dl_status conv2d_bwd_filter(const dl_conv_desc *d, const void *x, const void *dy
     if (e != hipSuccess) return DL_ERR_LAUNCH;
     e = dlk::launch_splitk_reduce(a.partial, plan.splits, g.w_elems, dw, d->dw_dtype, stream);
     return hip_status(e);
+}
+
+dl_status dl_conv_describe(const dl_conv_desc *d, int pass, char *buf, size_t buf_bytes)
+{
+    if (!d || !buf) return DL_ERR_NULL;
+    if (buf_bytes < 2) return DL_ERR_SHAPE;
+    Geometry g;
+    const dl_status st = check_desc(d, &g);
+    if (st != DL_OK) return st;
+    if (pass != DL_PASS_FWD && pass != DL_PASS_BWD_DATA && pass != DL_PASS_BWD_FILTER) return DL_ERR_UNSUPPORTED;
+    // The entry point itself runs, on stand-in addresses that only pointer arithmetic ever touches,
+    // with every launch turned into a log line.
+    void *const a = reinterpret_cast<void *>(uintptr_t(1) << 40);
+    void *const b = reinterpret_cast<void *>(uintptr_t(2) << 40);
+    void *const c = reinterpret_cast<void *>(uintptr_t(3) << 40);
+    void *const ws = reinterpret_cast<void *>(uintptr_t(4) << 40);
+    size_t ws_bytes = 0;
+    dl_conv_workspace_bytes(d, pass, &ws_bytes);
+    dlk::LaunchLog log;
+    dlk::launch_log = &log;
+    dl_status r;
+    if (pass == DL_PASS_FWD) r = conv2d_fwd(d, a, b, c, ws, ws_bytes, nullptr);
+    else if (pass == DL_PASS_BWD_DATA) r = conv2d_bwd_data(d, a, b, c, ws, ws_bytes, nullptr);
+    else r = conv2d_bwd_filter(d, a, b, c, ws, ws_bytes, nullptr);
+    dlk::launch_log = nullptr;
+    if (r != DL_OK) return r;
+    const size_t n = log.text.size() < buf_bytes - 1 ? log.text.size() : buf_bytes - 1;
+    log.text.copy(buf, n);
+    buf[n] = 0;
+    return DL_OK;
 }
 
 // The transposed convolution and its two gradients are the three passes of the underlying

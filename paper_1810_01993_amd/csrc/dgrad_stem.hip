@@ -156,9 +156,9 @@ hipError_t launch_dgrad_stem(const DgradStemArgs &a, bool is_bf16, hipStream_t s
     if (tiles <= 0 || tiles > 0x7fffffff || a.K > DS_MAXCH * BK || a.C > 16) return hipErrorInvalidValue;
     // the forward output extent of such a layer: every dy pixel the halo addresses is bounded by it
     if (a.P != (a.H - 1) / 2 + 1 || a.Q != (a.W - 1) / 2 + 1) return hipErrorInvalidValue;
-    if (is_bf16) hipLaunchKernelGGL(dgrad_stem_kernel<BF16>, dim3((unsigned)tiles), dim3(512), 0, stream, a);
-    else hipLaunchKernelGGL(dgrad_stem_kernel<F16>, dim3((unsigned)tiles), dim3(512), 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("dgrad_stem_kernel", dgrad_stem_kernel<BF16>, dim3((unsigned)tiles), dim3(512), 0, stream, a);
+    else DLK_LAUNCH("dgrad_stem_kernel", dgrad_stem_kernel<F16>, dim3((unsigned)tiles), dim3(512), 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

@@ -205,8 +205,8 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
     if (a.Cin % 8 != 0) {
         const int64_t tiles = ((M + 127) / 128) * ((a.Nout + 63) / 64);
         if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(igemm_scalar_kernel<T>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
-        return hipGetLastError();
+        DLK_LAUNCH("igemm_scalar_kernel", igemm_scalar_kernel<T>, dim3((unsigned)tiles), dim3(256), 0, stream, a);
+        return dlk::launch_status();
     }
     const int cfg = choose_cfg(a);
     if (cfg >= 100) {
@@ -326,8 +326,8 @@ hipError_t launch_zero_classes(uint16_t *dx, int N, int H, int W, int C, int sh,
     if (pieces <= 0 || mask == 0) return hipSuccess;
     const int64_t want = (pieces + 256 * 8 - 1) / (256 * 8);          // about eight pieces per thread
     const dim3 grid((unsigned)(want < 65535 ? want : 65535)), block(256);
-    hipLaunchKernelGGL(zero_classes_kernel, grid, block, 0, stream, dx, pieces, H, W, C / 8, sh, sw, mask);
-    return hipGetLastError();
+    DLK_LAUNCH("zero_classes_kernel", zero_classes_kernel, grid, block, 0, stream, dx, pieces, H, W, C / 8, sh, sw, mask);
+    return dlk::launch_status();
 }
 
 hipError_t launch_filter_relayout(const FilterRelayoutArgs &a, hipStream_t stream)
@@ -335,8 +335,8 @@ hipError_t launch_filter_relayout(const FilterRelayoutArgs &a, hipStream_t strea
     const int64_t total = (int64_t)a.C * a.TR * a.TS * a.K;
     if (total <= 0) return hipSuccess;
     const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
-    hipLaunchKernelGGL(filter_relayout_kernel, dim3(blocks), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    DLK_LAUNCH("filter_relayout_kernel", filter_relayout_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

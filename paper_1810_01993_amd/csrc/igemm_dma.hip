@@ -434,12 +434,12 @@ static hipError_t launch_dma_cfg(const IgemmArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)tiles, (unsigned)(a.c_outer && a.ksplits > 1 ? a.ksplits : 1)), block(WM * WN * 64);
     if (a.b_transposed) {
         if (!a.c_outer || a.Nout % 8 != 0) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true, true>), grid, block, 0, stream, a);
+        DLK_LAUNCH(kname("igemm_dma_kernel.bt", {BM, BN}), (igemm_dma_kernel<T, BM, BN, WM, WN, true, true>), grid, block, 0, stream, a);
     } else if (a.c_outer)
-        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, a);
+        DLK_LAUNCH(kname("igemm_dma_kernel.cmajor", {BM, BN}), (igemm_dma_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, a);
     else
-        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, a);
-    return hipGetLastError();
+        DLK_LAUNCH(kname("igemm_dma_kernel.tapmajor", {BM, BN}), (igemm_dma_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, a);
+    return dlk::launch_status();
 }
 
 template <class T>
@@ -469,9 +469,9 @@ static hipError_t launch_dma_batch_cfg(const IgemmBatch &b, hipStream_t stream)
     }
     if (tiles_max <= 0 || tiles_max * b.n > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(tiles_max * b.n)), block(WM * WN * 64);
-    if (b.a[0].b_transposed) hipLaunchKernelGGL((igemm_dma_batch_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((igemm_dma_batch_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, b);
-    return hipGetLastError();
+    if (b.a[0].b_transposed) DLK_LAUNCH(kname("igemm_dma_batch_kernel.bt", {BM, BN}), (igemm_dma_batch_kernel<T, BM, BN, WM, WN, true>), grid, block, 0, stream, b);
+    else DLK_LAUNCH(kname("igemm_dma_batch_kernel", {BM, BN}), (igemm_dma_batch_kernel<T, BM, BN, WM, WN, false>), grid, block, 0, stream, b);
+    return dlk::launch_status();
 }
 
 template <class T>

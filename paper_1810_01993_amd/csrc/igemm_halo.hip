@@ -306,15 +306,15 @@ hipError_t launch_igemm_halo(const IgemmArgs &a, bool is_bf16, hipStream_t strea
     const dim3 grid((unsigned)tiles), block(512);
     const int aw = halo_pieces_per_wave(a);
     if (aw == 3) {
-        if (is_bf16) hipLaunchKernelGGL((igemm_halo_kernel<BF16, 3>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((igemm_halo_kernel<F16, 3>), grid, block, 0, stream, a);
+        if (is_bf16) DLK_LAUNCH("igemm_halo_kernel<3>", (igemm_halo_kernel<BF16, 3>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("igemm_halo_kernel<3>", (igemm_halo_kernel<F16, 3>), grid, block, 0, stream, a);
     } else if (aw == 4) {
-        if (is_bf16) hipLaunchKernelGGL((igemm_halo_kernel<BF16, 4>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((igemm_halo_kernel<F16, 4>), grid, block, 0, stream, a);
+        if (is_bf16) DLK_LAUNCH("igemm_halo_kernel<4>", (igemm_halo_kernel<BF16, 4>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("igemm_halo_kernel<4>", (igemm_halo_kernel<F16, 4>), grid, block, 0, stream, a);
     } else {
         return hipErrorInvalidValue;
     }
-    return hipGetLastError();
+    return dlk::launch_status();
 }
 
 // ---- filter re-layout into [chunk][tap][row][32] --------------------------------
@@ -340,8 +340,8 @@ hipError_t launch_filter_block(const FilterBlockArgs &a, hipStream_t stream)
     const int64_t total = (int64_t)((a.Cin + BK - 1) / BK) * a.TR * a.TS * a.Nrows * BK;
     if (total <= 0) return hipSuccess;
     const int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    hipLaunchKernelGGL(filter_block_kernel, dim3(blocks), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    DLK_LAUNCH("filter_block_kernel", filter_block_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

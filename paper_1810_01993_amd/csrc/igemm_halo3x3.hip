@@ -353,9 +353,9 @@ hipError_t launch_columns(const IgemmArgs &a, bool is_bf16, hipStream_t stream, 
     w.Nout = ncols;
     w.D = a.D + col_first;
     if (a.bias) w.bias = a.bias + col_first;
-    if (is_bf16) hipLaunchKernelGGL((igemm_halo3x3_kernel<BF16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
-    else hipLaunchKernelGGL((igemm_halo3x3_kernel<F16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH(kname("igemm_halo3x3_kernel", {NB}), (igemm_halo3x3_kernel<BF16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
+    else DLK_LAUNCH(kname("igemm_halo3x3_kernel", {NB}), (igemm_halo3x3_kernel<F16, NB>), dim3((unsigned)tiles), dim3(512), 0, stream, w, col_first, a.Nout);
+    return dlk::launch_status();
 }
 }  // namespace
 

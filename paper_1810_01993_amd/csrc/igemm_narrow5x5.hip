@@ -440,9 +440,9 @@ hipError_t launch_igemm_wide5x5(const IgemmArgs &a, bool is_bf16, hipStream_t st
     const int ntiles_n = (a.Nout + 63) / 64;
     const int per_patch = (int)std::min<int64_t>(ntiles_n, std::max<int64_t>(1, 512 / tiles));
     const dim3 grid((unsigned)tiles, (unsigned)per_patch);
-    if (is_bf16) hipLaunchKernelGGL(igemm_wide5x5_kernel<BF16>, grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(igemm_wide5x5_kernel<F16>, grid, dim3(256), 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("igemm_wide5x5_kernel", igemm_wide5x5_kernel<BF16>, grid, dim3(256), 0, stream, a);
+    else DLK_LAUNCH("igemm_wide5x5_kernel", igemm_wide5x5_kernel<F16>, grid, dim3(256), 0, stream, a);
+    return dlk::launch_status();
 }
 
 hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
@@ -456,9 +456,9 @@ hipError_t launch_igemm_narrow5x5(const IgemmArgs &a, bool is_bf16, hipStream_t 
     b.split_chunks = cps;
     if (ks > 1 && !a.part) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles, (unsigned)ks);
-    if (is_bf16) hipLaunchKernelGGL(igemm_narrow5x5_kernel<BF16>, grid, dim3(256), 0, stream, b);
-    else hipLaunchKernelGGL(igemm_narrow5x5_kernel<F16>, grid, dim3(256), 0, stream, b);
-    hipError_t e = hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("igemm_narrow5x5_kernel", igemm_narrow5x5_kernel<BF16>, grid, dim3(256), 0, stream, b);
+    else DLK_LAUNCH("igemm_narrow5x5_kernel", igemm_narrow5x5_kernel<F16>, grid, dim3(256), 0, stream, b);
+    hipError_t e = dlk::launch_status();
     if (e != hipSuccess || ks == 1) return e;
     return launch_splitk_reduce_tail(a.part, ks, (int64_t)a.NB * a.OH * a.OW * a.Nout, a.D, is_bf16 ? 1 : 0, a.bias, a.relu,
                                      a.Nout, nullptr, stream);

@@ -4,11 +4,43 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <cstdio>
+#include <string>
 #ifdef DLCONV_TUNING
 #include <cstdlib>
 #endif
 
 namespace dlk {
+
+// Launch log.  dl_conv_describe() answers "which kernels would this call launch?" by walking the
+// very code of the entry point with this pointer set: every launch then appends its kernel's name
+// and grid to the log INSTEAD of launching, so the answer cannot drift from the dispatch.  The
+// pointer is thread-local and non-null only inside that query.
+struct LaunchLog { std::string text; };
+extern thread_local LaunchLog *launch_log;
+inline bool log_launch(const std::string &label, const dim3 &grid)
+{
+    if (!launch_log) return false;
+    char g[48];
+    if (grid.y > 1 || grid.z > 1) std::snprintf(g, sizeof g, "[%ux%ux%u]", grid.x, grid.y, grid.z);
+    else std::snprintf(g, sizeof g, "[%u]", grid.x);
+    if (!launch_log->text.empty()) launch_log->text += "; ";
+    launch_log->text += label + g;
+    return true;
+}
+// What a launch function returns after its launches: the runtime's verdict, or success while logging.
+inline hipError_t launch_status() { return launch_log ? hipSuccess : hipGetLastError(); }
+inline std::string kname(const char *base, std::initializer_list<int> params)
+{
+    std::string s = std::string(base) + "<";
+    bool first = true;
+    for (int v : params) { s += (first ? "" : ",") + std::to_string(v); first = false; }
+    return s + ">";
+}
+#define DLK_LAUNCH(label, kernel, grid, block, lds, stream, ...)                                       \
+    do {                                                                                               \
+        if (!dlk::log_launch(label, dim3(grid))) hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__); \
+    } while (0)
 
 // Sweep knobs.  The library as shipped has none: which kernel runs, with which tiles and in which
 // summation order, depends on the arguments of the call alone and never on the caller's

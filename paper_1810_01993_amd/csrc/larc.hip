@@ -139,11 +139,11 @@ template <class G>
 static hipError_t larc_launch(const LarcBatch &b, hipStream_t stream)
 {
     const dim3 grid(LARC_SLICES, (unsigned)b.n), block(LARC_THREADS);
-    hipLaunchKernelGGL(larc_norm_kernel<G>, grid, block, 0, stream, b);
-    hipError_t e = hipGetLastError();
+    DLK_LAUNCH("larc_norm_kernel", larc_norm_kernel<G>, grid, block, 0, stream, b);
+    hipError_t e = dlk::launch_status();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(larc_update_kernel<G>, grid, block, 0, stream, b);
-    return hipGetLastError();
+    DLK_LAUNCH("larc_update_kernel", larc_update_kernel<G>, grid, block, 0, stream, b);
+    return dlk::launch_status();
 }
 
 hipError_t launch_larc(const LarcBatch &b, int grad_dtype, hipStream_t stream)

@@ -283,11 +283,11 @@ hipError_t launch_logits_ce(const LogitsCeArgs &a, bool is_bf16, hipStream_t str
     const dim3 grid(logits_ce_blocks(a.n, a.C)), block(LC_THREADS);
     const int G = a.C / 8;
     const bool shfl = G == 32;                           // a pixel's threads are half a wavefront
-    if (is_bf16 && shfl) hipLaunchKernelGGL((logits_ce_kernel<BF16, true>), grid, block, 0, stream, a);
-    else if (is_bf16) hipLaunchKernelGGL((logits_ce_kernel<BF16, false>), grid, block, 0, stream, a);
-    else if (shfl) hipLaunchKernelGGL((logits_ce_kernel<F16, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((logits_ce_kernel<F16, false>), grid, block, 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16 && shfl) DLK_LAUNCH("logits_ce_kernel", (logits_ce_kernel<BF16, true>), grid, block, 0, stream, a);
+    else if (is_bf16) DLK_LAUNCH("logits_ce_kernel", (logits_ce_kernel<BF16, false>), grid, block, 0, stream, a);
+    else if (shfl) DLK_LAUNCH("logits_ce_kernel", (logits_ce_kernel<F16, true>), grid, block, 0, stream, a);
+    else DLK_LAUNCH("logits_ce_kernel", (logits_ce_kernel<F16, false>), grid, block, 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

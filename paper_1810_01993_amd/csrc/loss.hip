@@ -223,8 +223,8 @@ __global__ __launch_bounds__(CE_THREADS) void ce_finish_kernel(const float *__re
 
 hipError_t launch_ce_finish(const float *partials, int n_partials, float scale, float *loss, hipStream_t stream)
 {
-    hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, n_partials, scale, loss);
-    return hipGetLastError();
+    DLK_LAUNCH("ce_finish_kernel", ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, n_partials, scale, loss);
+    return dlk::launch_status();
 }
 
 hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_t *labels, const float *weights,
@@ -234,17 +234,17 @@ hipError_t launch_weighted_ce(const uint16_t *logits, bool is_bf16, const uint8_
     const int blocks = ce_num_blocks(n_pixels);
     const dim3 grid(blocks), block(CE_THREADS);
     if (is_bf16 && per_pixel)
-        hipLaunchKernelGGL((ce_kernel<BF16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+        DLK_LAUNCH("ce_kernel", (ce_kernel<BF16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
     else if (is_bf16)
-        hipLaunchKernelGGL((ce_kernel<BF16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+        DLK_LAUNCH("ce_kernel", (ce_kernel<BF16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
     else if (per_pixel)
-        hipLaunchKernelGGL((ce_kernel<F16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+        DLK_LAUNCH("ce_kernel", (ce_kernel<F16, true>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
     else
-        hipLaunchKernelGGL((ce_kernel<F16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
-    hipError_t e = hipGetLastError();
+        DLK_LAUNCH("ce_kernel", (ce_kernel<F16, false>), grid, block, 0, stream, logits, labels, weights, scale, n_pixels, dlogits, partials);
+    hipError_t e = dlk::launch_status();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, blocks, scale, loss);
-    return hipGetLastError();
+    DLK_LAUNCH("ce_finish_kernel", ce_finish_kernel, dim3(1), dim3(CE_THREADS), 0, stream, partials, blocks, scale, loss);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

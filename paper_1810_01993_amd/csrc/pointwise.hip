@@ -99,13 +99,13 @@ hipError_t launch_tail_bwd(const TailBwdArgs &a0, bool is_bf16, hipStream_t stre
     const int groups = (a.K + vec - 1) / vec, gpb = groups < TB_THREADS ? groups : TB_THREADS;
     const dim3 grid((unsigned)blocks, (unsigned)((groups + gpb - 1) / gpb)), block(TB_THREADS);
     if (vec == 8) {
-        if (is_bf16) hipLaunchKernelGGL((tail_bwd_kernel<BF16, 8>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((tail_bwd_kernel<F16, 8>), grid, block, 0, stream, a);
+        if (is_bf16) DLK_LAUNCH("tail_bwd_kernel", (tail_bwd_kernel<BF16, 8>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("tail_bwd_kernel", (tail_bwd_kernel<F16, 8>), grid, block, 0, stream, a);
     } else {
-        if (is_bf16) hipLaunchKernelGGL((tail_bwd_kernel<BF16, 1>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((tail_bwd_kernel<F16, 1>), grid, block, 0, stream, a);
+        if (is_bf16) DLK_LAUNCH("tail_bwd_kernel", (tail_bwd_kernel<BF16, 1>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("tail_bwd_kernel", (tail_bwd_kernel<F16, 1>), grid, block, 0, stream, a);
     }
-    hipError_t e = hipGetLastError();
+    hipError_t e = dlk::launch_status();
     if (e != hipSuccess) return e;
     return launch_splitk_reduce(a.partial, blocks, a.K, a.dbias, 2, stream);
 }

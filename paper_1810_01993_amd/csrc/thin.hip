@@ -90,9 +90,9 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
     if (per > 512) per = 512;
     const int64_t wg = (M + per - 1) / per;
     const dim3 grid((unsigned)(wg < 65535 ? wg : 65535), (unsigned)((groups + gpb - 1) / gpb)), block(256);
-    if (is_bf16) hipLaunchKernelGGL(thin_rows_kernel<BF16>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(thin_rows_kernel<F16>, grid, block, 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("thin_rows_kernel", thin_rows_kernel<BF16>, grid, block, 0, stream, a);
+    else DLK_LAUNCH("thin_rows_kernel", thin_rows_kernel<F16>, grid, block, 0, stream, a);
+    return dlk::launch_status();
 }
 
 // Filter gradient of a 1x1, stride-1, unpadded convolution with K <= THIN_MAX:
@@ -177,9 +177,9 @@ bool thin_wgrad_applicable(int K, int C, int R, int S, int sh, int sw, int ph, i
 hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 {
     const dim3 grid((unsigned)a.splits), block(256);
-    if (is_bf16) hipLaunchKernelGGL(thin_wgrad_kernel<BF16>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(thin_wgrad_kernel<F16>, grid, block, 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("thin_wgrad_kernel", thin_wgrad_kernel<BF16>, grid, block, 0, stream, a);
+    else DLK_LAUNCH("thin_wgrad_kernel", thin_wgrad_kernel<F16>, grid, block, 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

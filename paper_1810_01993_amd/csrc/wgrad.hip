@@ -215,14 +215,14 @@ static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)tiles, (unsigned)a.splits), block(WM * WN * 64);
     const bool va = a.K % 8 == 0, vb = a.C % 8 == 0;
     if (va && vb)
-        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, true, true>), grid, block, lds, stream, a);
+        DLK_LAUNCH(kname("wgrad_kernel", {BM, BN}), (wgrad_kernel<T, BM, BN, WM, WN, true, true>), grid, block, lds, stream, a);
     else if (vb)
-        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, false, true>), grid, block, lds, stream, a);
+        DLK_LAUNCH(kname("wgrad_kernel", {BM, BN}), (wgrad_kernel<T, BM, BN, WM, WN, false, true>), grid, block, lds, stream, a);
     else if (va)
-        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, true, false>), grid, block, lds, stream, a);
+        DLK_LAUNCH(kname("wgrad_kernel", {BM, BN}), (wgrad_kernel<T, BM, BN, WM, WN, true, false>), grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((wgrad_kernel<T, BM, BN, WM, WN, false, false>), grid, block, lds, stream, a);
-    return hipGetLastError();
+        DLK_LAUNCH(kname("wgrad_kernel", {BM, BN}), (wgrad_kernel<T, BM, BN, WM, WN, false, false>), grid, block, lds, stream, a);
+    return dlk::launch_status();
 }
 
 hipError_t launch_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
@@ -339,12 +339,12 @@ static hipError_t launch_reduce4(const float *partial, int32_t splits, int64_t n
     const int64_t want = (n + 255) / 256;
     const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
     if (out_dtype == 0)
-        hipLaunchKernelGGL(splitk_reduce4_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+        DLK_LAUNCH("splitk_reduce4_kernel", splitk_reduce4_kernel<0>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else if (out_dtype == 1)
-        hipLaunchKernelGGL(splitk_reduce4_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+        DLK_LAUNCH("splitk_reduce4_kernel", splitk_reduce4_kernel<1>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else
-        hipLaunchKernelGGL(splitk_reduce4_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
-    return hipGetLastError();
+        DLK_LAUNCH("splitk_reduce4_kernel", splitk_reduce4_kernel<2>, grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
+    return dlk::launch_status();
 }
 
 template <int G>
@@ -355,12 +355,12 @@ static hipError_t launch_reduce_g(const float *partial, int32_t splits, int64_t 
     const int64_t want = (n + XW - 1) / XW;
     const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
     if (out_dtype == 0)
-        hipLaunchKernelGGL((splitk_reduce_kernel<0, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+        DLK_LAUNCH(kname("splitk_reduce_kernel", {G}), (splitk_reduce_kernel<0, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else if (out_dtype == 1)
-        hipLaunchKernelGGL((splitk_reduce_kernel<1, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
+        DLK_LAUNCH(kname("splitk_reduce_kernel", {G}), (splitk_reduce_kernel<1, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, resid);
     else
-        hipLaunchKernelGGL((splitk_reduce_kernel<2, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
-    return hipGetLastError();
+        DLK_LAUNCH(kname("splitk_reduce_kernel", {G}), (splitk_reduce_kernel<2, G>), grid, block, 0, stream, partial, splits, n, out, bias, relu, ncols, nullptr);
+    return dlk::launch_status();
 }
 
 hipError_t launch_splitk_reduce_tail(const float *partial, int32_t splits, int64_t n, void *out, int out_dtype,

@@ -281,9 +281,9 @@ hipError_t launch_wgrad3x3(const WgradStripArgs &a, bool is_bf16, hipStream_t st
     // the slices must cover the image exactly as the kernel decodes them
     const int xblocks = (a.W + 31) / 32;
     if ((int64_t)a.N * ((a.H + a.rs - 1) / a.rs) * ((xblocks + a.xs - 1) / a.xs) != a.slices) return hipErrorInvalidValue;
-    if (is_bf16) hipLaunchKernelGGL(wgrad3x3_kernel<BF16>, dim3((unsigned)blocks), dim3(512), 0, stream, a);
-    else hipLaunchKernelGGL(wgrad3x3_kernel<F16>, dim3((unsigned)blocks), dim3(512), 0, stream, a);
-    return hipGetLastError();
+    if (is_bf16) DLK_LAUNCH("wgrad3x3_kernel", wgrad3x3_kernel<BF16>, dim3((unsigned)blocks), dim3(512), 0, stream, a);
+    else DLK_LAUNCH("wgrad3x3_kernel", wgrad3x3_kernel<F16>, dim3((unsigned)blocks), dim3(512), 0, stream, a);
+    return dlk::launch_status();
 }
 
 }  // namespace dlk

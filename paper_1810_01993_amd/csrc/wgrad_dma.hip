@@ -227,9 +227,9 @@ static hipError_t launch_cfg(const WgradArgs &a, hipStream_t stream)
     const int64_t split_groups = (a.splits + 7) / 8;        // each XCD takes every 8th slice
     const int64_t blocks = a.spread ? tiles * a.splits : tiles * split_groups * 8;
     if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((wgrad_dma_kernel<T, BM, BN, WM, WN, STAGES>), dim3((unsigned)blocks), dim3(WM * WN * 64), 0,
+    DLK_LAUNCH(kname("wgrad_dma_kernel", {BM, BN}), (wgrad_dma_kernel<T, BM, BN, WM, WN, STAGES>), dim3((unsigned)blocks), dim3(WM * WN * 64), 0,
                        stream, a);
-    return hipGetLastError();
+    return dlk::launch_status();
 }
 
 WgradPlan wgrad_make_plan(int64_t npix, int K, int C, int RSC, bool thin_ok)

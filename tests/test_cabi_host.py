@@ -28,6 +28,13 @@ def test_every_declared_symbol_is_exported(api):
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in dlconv.h but not exported"
     assert declared == set(api.EXPORTS)
+    # the measurement aids have a header of their own
+    probe = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "dlprobe.h")).read(), flags=re.S)
+    declared_probe = set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", probe))
+    assert declared_probe == set(api.PROBE_EXPORTS)
+    for name in declared_probe:
+        assert hasattr(lib, name), f"{name} is declared in dlprobe.h but not exported"
+    assert set(os.listdir(os.path.join(ROOT, "include"))) == {"dlconv.h", "dlprobe.h"}
 
 
 def test_out_shape_and_workspace_queries(api):
@@ -101,6 +108,11 @@ def test_pointer_checks_happen_before_any_launch(api):
     assert lib.larc_sgd_step(tp, 1, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, 16, 8, None) == 5
     assert lib.larc_sgd_step(None, 0, 0, f(.1), f(.02), f(0), f(0), f(0), 1, None, None, 0, None) == 0     # nothing to do
     assert lib.dl_status_string(0) == b"ok" and b"workspace" in lib.dl_status_string(5)
+    flop = ctypes.c_double()
+    assert lib.dl_probe_mfma(0, 0, 10, None, 16, ctypes.byref(flop), None) == 1
+    assert lib.dl_probe_mfma(2, 0, 10, 16, 16, ctypes.byref(flop), None) == 2
+    assert lib.dl_probe_stream(1, 16, None, 16, 3073, 16, None) == 2
+    assert lib.dl_probe_stream(3, 16, None, 16, 3072, 16, None) == 1
 
 
 _DISPATCH_PROBE = r"""
@@ -144,3 +156,22 @@ def test_dispatch_does_not_read_the_environment(api):
             assert "getenv" not in open(os.path.join(csrc, name)).read(), name
     syms = subprocess.run(["nm", "-D", "--undefined-only", api.LIB_PATH], capture_output=True, text=True, check=True).stdout
     assert "getenv" not in syms
+
+
+def test_describe_names_the_kernels_of_the_decoder_layers(api):
+    """dl_conv_describe runs the entry points' own dispatch with launches logged instead of issued
+    (no GPU needed): the layers that carry 87 % of the FLOPs must reach the kernels built for them."""
+    dec = api.ConvDesc(2, 768, 1152, 256, 256, 3, 3, 1, 1, 1, 1, 1, 1, api.DL_F16)
+    assert "igemm_halo3x3_kernel<4>[6912]" in api.dl_conv_describe(dec, api.PASS_FWD)
+    assert "igemm_halo3x3_kernel<4>[6912]" in api.dl_conv_describe(dec, api.PASS_BWD_DATA)
+    assert api.dl_conv_describe(dec, api.PASS_BWD_FILTER).startswith("wgrad3x3_kernel[")
+    dec304 = api.ConvDesc(2, 768, 1152, 304, 256, 3, 3, 1, 1, 1, 1, 1, 1, api.DL_BF16)
+    assert "igemm_halo3x3_kernel<5>[6912]" in api.dl_conv_describe(dec304, api.PASS_BWD_DATA)
+    stem = api.ConvDesc(2, 768, 1152, 16, 64, 7, 7, 2, 2, 3, 3, 1, 1, api.DL_F16)
+    assert "dgrad_stem_kernel" in api.dl_conv_describe(stem, api.PASS_BWD_DATA)
+    logits = api.ConvDesc(2, 768, 1152, 256, 3, 1, 1, 1, 1, 0, 0, 1, 1, api.DL_F16)
+    assert "thin_rows_kernel" in api.dl_conv_describe(logits, api.PASS_BWD_DATA)
+    assert "thin_wgrad_kernel" in api.dl_conv_describe(logits, api.PASS_BWD_FILTER)
+    # the query leaves nothing behind: a call after it still validates and reports as before
+    assert api._lib.conv2d_fwd(ctypes.byref(dec.c_struct()), None, None, None, None, 0, None) == 1
+    assert _code(api.dl_conv_describe, api.ConvDesc(2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, api.DL_F16), 5) == 6
