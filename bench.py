@@ -184,7 +184,7 @@ def loss_hbm_resident(api, torch, mult=64, probes=True):
     return out
 
 
-def mfma_microbench(api, torch, iters=20000):
+def mfma_microbench(api, torch, iters=100000):
     """Register-resident MFMA loops (no memory traffic) in this process, on this machine: what the matrix
     units sustain with constant operands and with operands distributed like the benchmark's (the chip
     is power-limited: the shader clock drops with the operands' switching activity).  Context for the

@@ -11,6 +11,8 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
@@ -41,6 +43,10 @@ struct F16 {
     static __device__ __forceinline__ float to_float(uint16_t h) {
         return (float)__builtin_bit_cast(_Float16, h);
     }
+    // two values rounded (nearest even) and packed, lo in bits 0..15: one v_cvt_pk_f16_f32
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        return __builtin_bit_cast(uint32_t, half2_t{(_Float16)lo, (_Float16)hi});
+    }
 };
 
 struct BF16 {
@@ -63,6 +69,10 @@ struct BF16 {
     }
     static __device__ __forceinline__ float to_float(uint16_t h) {
         return __builtin_bit_cast(float, (uint32_t)h << 16);
+    }
+    // two values rounded (nearest even) and packed, lo in bits 0..15: one v_cvt_pk_bf16_f32
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        return __builtin_bit_cast(uint32_t, bf16x2_t{(__bf16)lo, (__bf16)hi});
     }
 };
 
