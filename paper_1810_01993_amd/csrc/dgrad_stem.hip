@@ -30,7 +30,7 @@ constexpr int DS_TP = 16;                                // dy patch edge
 constexpr int DS_HW = DS_TP + 3;                         // halo edge: rows p0 - 1 .. p0 + 17
 constexpr int DS_PIECES = (DS_HW * DS_HW + 15) / 16;     // 16-pixel pieces of the halo image
 constexpr int DS_MAXCH = 2;                              // 32-channel chunks of K held at once
-__device__ __forceinline__ int ds_swz(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int ds_swz(int row) { return (row >> 1) & 3; }   // 16-row operands: conflict-free at any alignment
 }  // namespace
 
 template <class T>

@@ -37,7 +37,11 @@ namespace dlk {
 namespace {
 constexpr int P3_PH = 16, P3_PW = 32, P3_BN = 128;
 constexpr int P3_HH = P3_PH + 2, P3_HW = P3_PW + 2;
-__device__ __forceinline__ int p3_swz(int row) { return (row >> 2) & 3; }
+// Which 16-byte slice of a 64-byte row holds channel slice v: v ^ swz(row).  Lane l of a 16x16x32 MFMA operand
+// reads slice l/16 of row l%16; with this rule a wavefront's ds_read_b128 of 16 consecutive rows takes its
+// 4 cycles (256 B per cycle) at any alignment of the first row (measured with the LDS counters; the rule
+// (row >> 2) & 3, right for 32-row operands, costs 8 cycles here).
+__device__ __forceinline__ int p3_swz(int row) { return (row >> 1) & 3; }
 }  // namespace
 
 // NB: 16-channel blocks per wave (4: the 128-channel tile; 5: a 160-channel tile, for channel

@@ -35,7 +35,7 @@ namespace dlk {
 namespace {
 constexpr int N5_PH = 16, N5_PW = 32, N5_T = 5, N5_BN = 32;
 constexpr int N5_HH = N5_PH + N5_T - 1, N5_HW = N5_PW + N5_T - 1;       // 20 x 36
-__device__ __forceinline__ int n5_swz(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int n5_swz(int row) { return (row >> 1) & 3; }   // 16-row operands: conflict-free at any alignment
 }  // namespace
 
 template <class T>
