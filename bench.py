@@ -345,8 +345,8 @@ def tiramisu_table(args):
 
 def config_table(args):
     """Configurations 1-4 (the parity cases that are not the headline): every layer and pass in the
-    configuration's own dtype, median HIP-event time over --steps calls with rotating buffer sets
-    (so that the 1x1 layers do not re-read cache-resident tensors), and beside it the fp64 oracle
+    configuration's own dtype, median HIP-event time per call over groups of back-to-back calls on
+    rotating buffer sets (so that the 1x1 layers do not re-read cache-resident tensors), and beside it the fp64 oracle
     on the very same layer in full, on the host cores (a baseline, not a target)."""
     import torch
     import oracle
@@ -391,14 +391,18 @@ def config_table(args):
             for i in range(max(args.warmup, nsets)):
                 fn(sets[i % nsets])
             torch.cuda.synchronize()
+            # groups of back-to-back calls between two events (launch latency is not what is measured),
+            # each call on the next buffer set
+            reps = 10 if layer.flops() < 1e11 else 3
             ts = []
-            for i in range(max(args.steps, 20)):
+            for g in range(max(args.steps, 10)):
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
-                fn(sets[i % nsets])
+                for i in range(reps):
+                    fn(sets[(g * reps + i) % nsets])
                 b.record()
                 torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b))
+                ts.append(a.elapsed_time(b) / reps)
             ms = float(np.median(ts))
             t0 = time.perf_counter()
             orc()

@@ -300,7 +300,7 @@ dl_status dl_conv_workspace_bytes(const dl_conv_desc *desc, int pass, size_t *by
             // with a residual input some kernels are not available and the choice of scratch changes: enough for either
             dlk::IgemmArgs a = fwd_args(desc, g);
             const size_t plain = igemm_scratch_bytes(a);
-            a.resid = reinterpret_cast<const uint16_t *>(a.resid) + 8;      // any non-null value: only tested for null
+            a.resid = reinterpret_cast<const uint16_t *>(uintptr_t(16));     // any non-null value: only tested for null
             *bytes = std::max(plain, igemm_scratch_bytes(a));
             return DL_OK;
         }
