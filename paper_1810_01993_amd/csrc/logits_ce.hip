@@ -132,17 +132,23 @@ __global__ __launch_bounds__(LC_THREADS, 3) void logits_ce_kernel(const LogitsCe
         // One pixel's logits -> loss term and dz (the arithmetic of the loss kernel), copies on request.
         struct Dz { float d0, d1, d2, loss; };
         auto pixel = [](float z0, float z1, float z2, int lab, float w0, float w1, float w2, float scale) __attribute__((always_inline)) {
-            const float wl = lab == 0 ? w0 : (lab == 1 ? w1 : (lab == 2 ? w2 : 0.f));   // labels outside {0,1,2}: weight 0
+            // selects, raw v_log_f32 / v_rcp_f32 (the sum of the exponentials lies in [1, 3]): as in the loss kernel
+            const bool is0 = lab == 0, is1 = lab == 1, is2 = lab == 2;
+            float wl = is1 ? w1 : w0;
+            wl = is2 ? w2 : wl;
+            wl = (is0 | is1 | is2) ? wl : 0.f;                                          // labels outside {0,1,2}: weight 0
             const float m = fmaxf(z0, fmaxf(z1, z2));
             const float e0 = __expf(z0 - m), e1 = __expf(z1 - m), e2 = __expf(z2 - m);
             const float se = e0 + e1 + e2;
-            const float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
-            const float gsc = scale * wl / se;
+            float zl = is1 ? z1 : z2;
+            zl = is0 ? z0 : zl;
+            const float sw = scale * wl;
+            const float gsc = sw * __builtin_amdgcn_rcpf(se);
             Dz r;
-            r.d0 = gsc * e0 - (lab == 0 ? scale * wl : 0.f);
-            r.d1 = gsc * e1 - (lab == 1 ? scale * wl : 0.f);
-            r.d2 = gsc * e2 - (lab == 2 ? scale * wl : 0.f);
-            r.loss = wl * (m + __logf(se) - zl);
+            r.d0 = fmaf(gsc, e0, is0 ? -sw : 0.f);
+            r.d1 = fmaf(gsc, e1, is1 ? -sw : 0.f);
+            r.d2 = fmaf(gsc, e2, is2 ? -sw : 0.f);
+            r.loss = wl * ((m - zl) + 0.693147180559945f * __builtin_amdgcn_logf(se));
             return r;
         };
         // the copies of the logits and of their gradient, rounded on store, and the pixel's loss term
