@@ -114,10 +114,10 @@ class LayerState:
 
 def cpu_baseline():
     """The fp64 oracle, as it stands, on a bounded sample of the same workload:
-    forward + data gradient + filter gradient of a 24-row slab of one image of
+    forward + data gradient + filter gradient of a 128-row slab of one image of
     the 3x3 256->256 full-resolution decoder layer."""
     import oracle
-    rows = 24
+    rows = 128
     s = oracle.ConvShape(1, rows, 1152, 256, 256, 3, 3, 1, 1, 1)
     g = np.random.default_rng(0)
     x = np.abs(g.standard_normal((1, rows, 1152, 256)))
