@@ -359,7 +359,7 @@ def config_table(args):
     if os.environ.get("OMP_NUM_THREADS"):
         cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
     print(f"# config {args.config}, {dtype}, fp32 accumulate; oracle: fp64 on {cores} host cores", flush=True)
-    print(f"{'layer':24s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s} "
+    print(f"{'layer':24s} {'pass':6s} {'ms':>9s} {'p16':>8s} {'p84':>8s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s} "
           f"{'oracle s':>9s} {'oracle GFLOP/s':>14s}  kernels", flush=True)
     tot_ms, tot_flop, tot_orc = 0.0, 0.0, 0.0
     for li, layer in enumerate(table):
@@ -412,7 +412,8 @@ def config_table(args):
             tot_ms += ms
             tot_flop += layer.flops()
             tot_orc += osec
-            print(f"{layer.name:24s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
+            lo, hi = np.percentile(ts, [16, 84])
+            print(f"{layer.name:24s} {which:6s} {ms:9.4f} {lo:8.4f} {hi:8.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
                   f"{100 * gbs / HBM_PEAK_GBS:6.1f} {osec:9.2f} {layer.flops() / osec / 1e9:14.1f}  "
                   f"{api.dl_conv_describe(desc, pid)}", flush=True)
         del sets
@@ -539,14 +540,22 @@ def main():
         step()
     torch.cuda.synchronize()
     all_events = []
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]    # step boundaries on the main stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for k in range(args.steps):
         ev = []
+        marks[k].record()
         step(ev)
         all_events.append(ev)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    # the paper's throughput statistic (Sec. "Performance Measurement"): median over the steps, with the
+    # 0.16 and 0.84 percentiles as the error bar
+    per_step = np.array([marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)])
+    step_stat = {"median": float(np.median(per_step)), "p16": float(np.percentile(per_step, 16)),
+                 "p84": float(np.percentile(per_step, 84))}
 
     # per-call device times from the HIP events recorded inside the timed region
     times = {}
@@ -578,7 +587,7 @@ def main():
     loss_ms = med[("loss", "loss")]
 
     if args.table:
-        print(f"{'layer':28s} {'pass':6s} {'ms':>9s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s}",
+        print(f"{'layer':28s} {'pass':6s} {'ms':>9s} {'p16':>8s} {'p84':>8s} {'TFLOP/s':>9s} {'%MFMA':>6s} {'GB/s(min)':>10s} {'%HBM':>6s}",
               file=sys.stderr)
         for i, st in enumerate(net):
             for which in ("fwd", "dgrad", "wgrad"):
@@ -587,7 +596,8 @@ def main():
                 ms = med[(i, which)]
                 tf = st.layer.flops() / (ms * 1e-3) / 1e12
                 gbs = st.layer.bytes_fwd() / (ms * 1e-3) / 1e9
-                print(f"{st.layer.name:28s} {which:6s} {ms:9.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
+                lo, hi = np.percentile(times[(i, which)], [16, 84])
+                print(f"{st.layer.name:28s} {which:6s} {ms:9.4f} {lo:8.4f} {hi:8.4f} {tf:9.1f} {100 * tf / MFMA_PEAK_TFLOPS:6.1f} {gbs:10.0f} "
                       f"{100 * gbs / HBM_PEAK_GBS:6.1f}", file=sys.stderr)
         print(f"loss: {loss_ms:.4f} ms  ({13 * n_pix / (loss_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)", file=sys.stderr)
         print(f"sum of per-call medians: conv {conv_ms:.3f} ms, loss {loss_ms:.4f} ms; wall {ms_per_step:.3f} ms/step",
@@ -620,6 +630,8 @@ def main():
         "config": {"workload": f"config5: DeepLabv3+ conv stack + loss, N=2, 1152x768x16, {'bf16' if args.dtype == 'bf16' else 'fp16'} in / fp32 accumulate",
                    "streams": args.streams, "activations": args.activations, "fused_logits": bool(args.fused_logits),
                    "flop_per_step": step_flops, "frac_of_mfma_peak": value / MFMA_PEAK_TFLOPS,
+                   "step_ms": step_stat,
+                   "tflops_median_p16_p84": [step_flops / (step_stat[q] * 1e-3) / 1e12 for q in ("median", "p84", "p16")],
                    "conv_ms_sum_of_medians": conv_ms, "loss_ms": loss_ms,
                    "loss_gbs": 13 * n_pix / (loss_ms * 1e-3) / 1e9,
                    "loss_hbm_resident": loss_big, "mfma_microbench": micro},
