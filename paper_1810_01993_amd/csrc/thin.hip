@@ -3,6 +3,8 @@
 // gradient are bandwidth-bound outer-product / dot-product sweeps over the
 // 256-channel activation tensor, and an MFMA tile padded from 3 to 32 would
 // only add latency.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -16,55 +18,64 @@ constexpr int THIN_MAX = 4;      // channels on the thin side
 // walks down them: one 16-byte store per Cin LDS broadcast reads, no global load between two stores (with the
 // A values read from memory row by row the sweep took 0.30 instead of 0.23 ms on the logits layer whenever
 // other kernels had run since the last call, as in a training step).
-template <class T>
+// CIN: the number of input channels (1..THIN_MAX) known at compile time; TAIL: bias, ReLU or a residual
+// input present.  (With both read at run time the row loop held ~100 vector instructions and 16 branches
+// per 16-byte store and the instruction issue, not memory, bounded the sweep.)
+template <class T, int CIN, bool TAIL>
 __global__ __launch_bounds__(256) void thin_rows_kernel(const IgemmArgs p)
 {
     constexpr int SUB = 512;
-    __shared__ float sa[SUB * THIN_MAX];
+    __shared__ __align__(16) float sa[SUB * THIN_MAX];
     const int groups = p.Nout / 8;
     const int gpb = groups < 256 ? groups : 256;
     const int rows_pb = 256 / gpb;
     const int g = blockIdx.y * gpb + threadIdx.x % gpb, r = threadIdx.x / gpb;
     const bool active = r < rows_pb && g < groups;
     const int j = active ? g * 8 : 0;
-    float b[8][THIN_MAX];
+    float b[8][CIN];
 #pragma unroll
     for (int e = 0; e < 8; ++e)
 #pragma unroll
-        for (int c = 0; c < THIN_MAX; ++c) b[e][c] = c < p.Cin ? T::to_float(p.B[(size_t)(j + e) * p.Cin + c]) : 0.f;
+        for (int c = 0; c < CIN; ++c) b[e][c] = T::to_float(p.B[(size_t)(j + e) * CIN + c]);
     const int64_t M = (int64_t)p.NB * p.OH * p.OW;
     const int64_t chunk = (M + gridDim.x - 1) / gridDim.x;
     const int64_t m_begin = (int64_t)blockIdx.x * chunk, m_end = m_begin + chunk < M ? m_begin + chunk : M;
     for (int64_t sub = m_begin; sub < m_end; sub += SUB) {
         const int n = (int)(m_end - sub < SUB ? m_end - sub : SUB);
         __syncthreads();
-        for (int i = threadIdx.x; i < n * p.Cin; i += 256) {
-            const int row = i / p.Cin, c = i - row * p.Cin;
-            sa[row * THIN_MAX + c] = T::to_float(p.A[sub * p.Cin + i]);
+        for (int i = threadIdx.x; i < n * CIN; i += 256) {
+            const int row = i / CIN, c = i - row * CIN;
+            sa[row * THIN_MAX + c] = T::to_float(p.A[sub * CIN + i]);
         }
         __syncthreads();
         if (!active) continue;
+        uint16_t *dst = p.D + (sub + r) * p.ldd + j;
+        const size_t dstep = (size_t)rows_pb * p.ldd;
 #pragma unroll 4
-        for (int q = r; q < n; q += rows_pb) {
-            const int64_t m = sub + q;
-            float a[THIN_MAX];
-#pragma unroll
-            for (int c = 0; c < THIN_MAX; ++c) a[c] = c < p.Cin ? sa[q * THIN_MAX + c] : 0.f;
+        for (int q = r; q < n; q += rows_pb, dst += dstep) {
+            const floatx4_t a4 = *reinterpret_cast<const floatx4_t *>(sa + q * THIN_MAX);   // one 16-byte broadcast read
             u32x4_t out, rv{0, 0, 0, 0};
-            if (p.resid) rv = *reinterpret_cast<const u32x4_t *>(p.resid + m * p.ldd + j);
+            if constexpr (TAIL)
+                if (p.resid) rv = *reinterpret_cast<const u32x4_t *>(p.resid + (sub + q) * p.ldd + j);
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
-                float s0 = T::to_float((uint16_t)(rv[e >> 1] & 0xffffu)), s1 = T::to_float((uint16_t)(rv[e >> 1] >> 16));
-#pragma unroll
-                for (int c = 0; c < THIN_MAX; ++c) {
-                    s0 += a[c] * b[e][c];
-                    s1 += a[c] * b[e + 1][c];
+                float s0 = 0.f, s1 = 0.f;
+                if constexpr (TAIL) {
+                    s0 = T::to_float((uint16_t)(rv[e >> 1] & 0xffffu));
+                    s1 = T::to_float((uint16_t)(rv[e >> 1] >> 16));
                 }
-                s0 = apply_tail(s0, p.bias, p.relu, j + e);
-                s1 = apply_tail(s1, p.bias, p.relu, j + e + 1);
-                out[e >> 1] = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+#pragma unroll
+                for (int c = 0; c < CIN; ++c) {
+                    s0 += a4[c] * b[e][c];
+                    s1 += a4[c] * b[e + 1][c];
+                }
+                if constexpr (TAIL) {
+                    s0 = apply_tail(s0, p.bias, p.relu, j + e);
+                    s1 = apply_tail(s1, p.bias, p.relu, j + e + 1);
+                }
+                out[e >> 1] = T::pack2(s0, s1);
             }
-            __builtin_nontemporal_store(out, reinterpret_cast<u32x4_t *>(p.D + m * p.ldd + j));
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4_t *>(dst));
         }
     }
 }
@@ -90,8 +101,24 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
     if (per > 512) per = 512;
     const int64_t wg = (M + per - 1) / per;
     const dim3 grid((unsigned)(wg < 65535 ? wg : 65535), (unsigned)((groups + gpb - 1) / gpb)), block(256);
-    if (is_bf16) DLK_LAUNCH("thin_rows_kernel", thin_rows_kernel<BF16>, grid, block, 0, stream, a);
-    else DLK_LAUNCH("thin_rows_kernel", thin_rows_kernel<F16>, grid, block, 0, stream, a);
+    const bool tail = a.bias || a.relu || a.resid;
+    auto go = [&](auto cin, auto has_tail) {
+        constexpr int CIN = decltype(cin)::value;
+        constexpr bool TAIL = decltype(has_tail)::value;
+        if (is_bf16) DLK_LAUNCH("thin_rows_kernel", (thin_rows_kernel<BF16, CIN, TAIL>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("thin_rows_kernel", (thin_rows_kernel<F16, CIN, TAIL>), grid, block, 0, stream, a);
+    };
+    auto by_tail = [&](auto cin) {
+        if (tail) go(cin, std::true_type{});
+        else go(cin, std::false_type{});
+    };
+    switch (a.Cin) {
+        case 1: by_tail(std::integral_constant<int, 1>{}); break;
+        case 2: by_tail(std::integral_constant<int, 2>{}); break;
+        case 3: by_tail(std::integral_constant<int, 3>{}); break;
+        case 4: by_tail(std::integral_constant<int, 4>{}); break;
+        default: return hipErrorInvalidValue;
+    }
     return dlk::launch_status();
 }
 
@@ -101,61 +128,81 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
 // keeps K x 8 running sums, the pixel lanes are then added in a fixed order.
 // The workgroup's slice of dy is staged in LDS as fp32, 512 pixels at a time, so
 // that the inner loop issues one 16-byte global load per pixel and nothing else.
-template <class T>
+// KK: the number of output channels (1..THIN_MAX) at compile time, so that the pixel loop is free of
+// branches and the loads of four pixels are in flight before the first is used (with K read at run
+// time every load was awaited right after its issue).  The sums of a thread run over its pixels in
+// ascending order either way.
+template <class T, int KK>
 __global__ __launch_bounds__(256) void thin_wgrad_kernel(const WgradArgs p)
 {
     constexpr int SUB = 512;                             // pixels of dy staged at a time
     __shared__ float red[256 * 8];                       // 8 sums per thread, reused for each k
-    __shared__ float sdy[SUB * THIN_MAX];
+    __shared__ __align__(16) float sdy[SUB * THIN_MAX];
     const int groups = p.C / 8;                          // <= 256
     const int lanes = 256 / groups;                      // pixel lanes per workgroup
     const int g = threadIdx.x % groups, pl = threadIdx.x / groups;
     const int npix = p.N * p.P * p.Q;
     const int pix_begin = blockIdx.x * p.chunk, pix_end = min(npix, pix_begin + p.chunk);
-    float acc[THIN_MAX][8];
+    float acc[KK][8];
 #pragma unroll
-    for (int k = 0; k < THIN_MAX; ++k)
+    for (int k = 0; k < KK; ++k)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[k][e] = 0.f;
+    auto add_pixel = [&](const u32x4_t xv, const int px) {
+        const floatx4_t gd = *reinterpret_cast<const floatx4_t *>(sdy + px * THIN_MAX);   // one 16-byte broadcast read
+        float xf[8];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            xf[2 * d] = T::to_float((uint16_t)(xv[d] & 0xffffu));
+            xf[2 * d + 1] = T::to_float((uint16_t)(xv[d] >> 16));
+        }
+#pragma unroll
+        for (int k = 0; k < KK; ++k)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[k][e] += gd[k] * xf[e];
+    };
     for (int sub = pix_begin; sub < pix_end; sub += SUB) {
         const int sub_end = min(pix_end, sub + SUB);
         __syncthreads();                                 // the previous part of dy is no longer read
-        for (int i = threadIdx.x; i < (sub_end - sub) * p.K; i += 256) {
-            const int px = i / p.K, k = i - px * p.K;
-            sdy[px * THIN_MAX + k] = T::to_float(p.dy[(size_t)sub * p.K + i]);
+        for (int i = threadIdx.x; i < (sub_end - sub) * KK; i += 256) {
+            const int px = i / KK, k = i - px * KK;
+            sdy[px * THIN_MAX + k] = T::to_float(p.dy[(size_t)sub * KK + i]);
         }
         __syncthreads();
         if (pl < lanes) {
-#pragma unroll 4
-            for (int pix = sub + pl; pix < sub_end; pix += lanes) {
-                const u32x4_t xv = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p.x + (size_t)pix * p.C + g * 8));
-                float xf[8];
+            const uint16_t *src = p.x + (size_t)(sub + pl) * p.C + g * 8;
+            const size_t step = (size_t)lanes * p.C;
+            // this lane's pixels of the part: n_l of them, `lanes` apart; groups of four are fetched one
+            // group ahead of the arithmetic (the scheduling barriers keep the loads where they are written)
+            const int n_l = (sub_end - sub - pl + lanes - 1) / lanes;
+            const int ngroups = n_l >> 2;
+            int px = pl;                                 // pixel within the part
+            auto load4 = [&](u32x4_t (&v)[4], const uint16_t *q) {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    xf[2 * d] = T::to_float((uint16_t)(xv[d] & 0xffffu));
-                    xf[2 * d + 1] = T::to_float((uint16_t)(xv[d] >> 16));
-                }
-                const float *gd = sdy + (pix - sub) * THIN_MAX;
+                for (int i = 0; i < 4; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(q + i * step));
+            };
+            u32x4_t cur[4], nxt[4];
+            if (ngroups > 0) load4(cur, src);
+            for (int gi = 0; gi < ngroups; ++gi, px += 4 * lanes) {
+                src += 4 * step;
+                if (gi + 1 < ngroups) load4(nxt, src);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int k = 0; k < THIN_MAX; ++k)
-                    if (k < p.K) {
-                        const float gk = gd[k];
+                for (int i = 0; i < 4; ++i) add_pixel(cur[i], px + i * lanes);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[k][e] += gk * xf[e];
-                    }
+                for (int i = 0; i < 4; ++i) cur[i] = nxt[i];
             }
+            for (; px < sub_end - sub; px += lanes, src += step)
+                add_pixel(__builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src)), px);
         }
     }
-    float *out = p.partial + (size_t)blockIdx.x * p.K * p.C;
-    for (int k = 0; k < p.K; ++k) {
+    float *out = p.partial + (size_t)blockIdx.x * KK * p.C;
+#pragma unroll
+    for (int k = 0; k < KK; ++k) {
         __syncthreads();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < THIN_MAX; ++kk) if (kk == k) v = acc[kk][e];
-            red[threadIdx.x * 8 + e] = (pl < lanes) ? v : 0.f;
-        }
+        for (int e = 0; e < 8; ++e) red[threadIdx.x * 8 + e] = (pl < lanes) ? acc[k][e] : 0.f;
         __syncthreads();
         if (pl == 0) {
 #pragma unroll
@@ -177,8 +224,18 @@ bool thin_wgrad_applicable(int K, int C, int R, int S, int sh, int sw, int ph, i
 hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream)
 {
     const dim3 grid((unsigned)a.splits), block(256);
-    if (is_bf16) DLK_LAUNCH("thin_wgrad_kernel", thin_wgrad_kernel<BF16>, grid, block, 0, stream, a);
-    else DLK_LAUNCH("thin_wgrad_kernel", thin_wgrad_kernel<F16>, grid, block, 0, stream, a);
+    auto go = [&](auto kk) {
+        constexpr int KK = decltype(kk)::value;
+        if (is_bf16) DLK_LAUNCH("thin_wgrad_kernel", (thin_wgrad_kernel<BF16, KK>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("thin_wgrad_kernel", (thin_wgrad_kernel<F16, KK>), grid, block, 0, stream, a);
+    };
+    switch (a.K) {
+        case 1: go(std::integral_constant<int, 1>{}); break;
+        case 2: go(std::integral_constant<int, 2>{}); break;
+        case 3: go(std::integral_constant<int, 3>{}); break;
+        case 4: go(std::integral_constant<int, 4>{}); break;
+        default: return hipErrorInvalidValue;
+    }
     return dlk::launch_status();
 }
 
