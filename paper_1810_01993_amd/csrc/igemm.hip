@@ -202,6 +202,7 @@ static hipError_t dispatch(const IgemmArgs &a, hipStream_t stream)
 {
     const int64_t M = (int64_t)a.NB * a.OH * a.OW;
     if (forced_cfg() < 0 && thin_rows_applicable(a)) return launch_thin_rows(a, std::is_same<T, BF16>::value, stream);
+    if (forced_cfg() < 0 && thin_cols_applicable(a)) return launch_thin_cols(a, std::is_same<T, BF16>::value, stream);
     if (a.Cin % 8 != 0) {
         const int64_t tiles = ((M + 127) / 128) * ((a.Nout + 63) / 64);
         if (tiles <= 0 || tiles > 0x7fffffff) return hipErrorInvalidValue;
@@ -260,7 +261,7 @@ int igemm_batch_cfg(const IgemmArgs *a, int n)
     int cfg = -1;
     for (int i = 0; i < n; ++i) {
         const IgemmArgs &g = a[i];
-        if (g.Cin % 8 != 0 || thin_rows_applicable(g) || !choose_c_outer(g) || g.b_transposed != a[0].b_transposed) return -1;
+        if (g.Cin % 8 != 0 || thin_rows_applicable(g) || thin_cols_applicable(g) || !choose_c_outer(g) || g.b_transposed != a[0].b_transposed) return -1;
         int cps;
         if (choose_ksplits(g, &cps) > 1) return -1;
         const int c = choose_cfg(g);

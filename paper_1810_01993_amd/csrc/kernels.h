@@ -233,6 +233,8 @@ hipError_t launch_wgrad5x5(const WgradStripArgs &a, bool is_bf16, hipStream_t st
 // Streaming kernels for 1x1 layers with <= 4 channels on one side (cfg -2 of the plan).
 bool thin_rows_applicable(const IgemmArgs &a);
 hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
+bool thin_cols_applicable(const IgemmArgs &a);
+hipError_t launch_thin_cols(const IgemmArgs &a, bool is_bf16, hipStream_t stream);
 bool thin_wgrad_applicable(int K, int C, int R, int S, int sh, int sw, int ph, int pw);
 hipError_t launch_thin_wgrad(const WgradArgs &a, bool is_bf16, hipStream_t stream);
 

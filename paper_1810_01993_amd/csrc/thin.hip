@@ -122,6 +122,152 @@ hipError_t launch_thin_rows(const IgemmArgs &a, bool is_bf16, hipStream_t stream
     return dlk::launch_status();
 }
 
+// Forward pass with a handful of OUTPUT channels and 256 input channels (the logits layer):
+//   D[m][k] = sum_{c < 256} A[m][c] * B[k][c],  k < KK <= THIN_MAX, dense rows of KK values.
+// A bandwidth-bound sweep over A.  A lane owns one 16-byte chunk (8 channels) of a pixel and keeps the
+// matching filter values in registers; the 32 lanes of a pixel (half a wavefront) add their partial dot
+// products with four DPP row shifts and a row broadcast, lanes 31 and 63 park the two pixels' sums in LDS
+// and the lanes that will store them read them back.  A wavefront works through runs of 16 consecutive pixels
+// (8 trips of 1 KB), the next run's loads issued before the current run's arithmetic, and writes a run's
+// 16 * KK results as one contiguous row of 2-byte stores.  Every sum is formed in a fixed order.
+constexpr int TC_CIN = 256, TC_RUN = 16;
+
+template <class T, int KK, bool TAIL>
+__global__ __launch_bounds__(256) void thin_cols_kernel(const IgemmArgs p)
+{
+    __shared__ float sy[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane & 31, half = lane >> 5;
+    float w[KK][8];
+#pragma unroll
+    for (int k = 0; k < KK; ++k) {
+        const u32x4_t wv = *reinterpret_cast<const u32x4_t *>(p.B + (size_t)k * TC_CIN + g * 8);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            w[k][2 * d] = T::to_float((uint16_t)(wv[d] & 0xffffu));
+            w[k][2 * d + 1] = T::to_float((uint16_t)(wv[d] >> 16));
+        }
+    }
+    const int64_t M = (int64_t)p.NB * p.OH * p.OW;
+    const int64_t runs = (M + TC_RUN - 1) / TC_RUN, stride = (int64_t)gridDim.x * 4;
+    auto load_run = [&](u32x4_t (&v)[8], int64_t run) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            int64_t m = run * TC_RUN + 2 * t + half;             // past the end (last run only): re-read the last pixel,
+            m = m < M ? m : M - 1;                               // its results are not stored
+            v[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p.A + m * TC_CIN + g * 8));
+        }
+    };
+    auto shr = [](float t, auto ctrl) {      // row_shr:n reads lane - n of the same row of 16 lanes, zero outside it
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    // the arithmetic of one run whose chunks are in `x`
+    auto process = [&](const u32x4_t (&x)[8], const int64_t run) {
+        // the 8 * KK dot products of the run stage by stage (independent chains side by side, so that the
+        // DPP steps do not wait on each other)
+        float v[8][KK];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            float xf[8];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                xf[2 * d] = T::to_float((uint16_t)(x[t][d] & 0xffffu));
+                xf[2 * d + 1] = T::to_float((uint16_t)(x[t][d] >> 16));
+            }
+#pragma unroll
+            for (int k = 0; k < KK; ++k) {
+                float a = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a += xf[e] * w[k][e];
+                v[t][k] = a;
+            }
+        }
+        auto all_chains = [&](auto ctrl) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int k = 0; k < KK; ++k) v[t][k] += shr(v[t][k], ctrl);
+        };
+        all_chains(std::integral_constant<int, 0x111>{});
+        all_chains(std::integral_constant<int, 0x112>{});
+        all_chains(std::integral_constant<int, 0x114>{});
+        all_chains(std::integral_constant<int, 0x118>{});        // lane 15 of every row of 16: the row's sum
+        // row_bcast:15 into rows 1 and 3: lanes 31 and 63 then hold the sums of the trip's two pixels;
+        // they park them in the wavefront's LDS row, from where lane i picks up result i of the run
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int k = 0; k < KK; ++k)
+                v[t][k] += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[t][k]), 0x142, 0xa, 0xf, false));
+        if (g == 31) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int k = 0; k < KK; ++k) sy[wave][(2 * t + half) * KK + k] = v[t][k];
+        }
+        const float outv = sy[wave][lane];               // same wavefront: LDS operations complete in order
+        const int64_t first = run * TC_RUN * KK;             // flat index of the run's first result
+        if (lane < TC_RUN * KK && first + lane < M * KK) {
+            float r = outv;
+            if constexpr (TAIL) r = apply_tail(r, p.bias, p.relu, lane % KK);
+            p.D[first + lane] = T::from_float(r);
+        }
+    };
+    // two register sets take turns: the loads of the run after next are issued before a run's arithmetic
+    int64_t run = (int64_t)blockIdx.x * 4 + wave;
+    u32x4_t xa[8], xb[8];
+    if (run < runs) load_run(xa, run);
+    while (run < runs) {
+        if (run + stride < runs) load_run(xb, run + stride);
+        __builtin_amdgcn_sched_barrier(0);
+        process(xa, run);
+        __builtin_amdgcn_sched_barrier(0);
+        run += stride;
+        if (run >= runs) break;
+        if (run + stride < runs) load_run(xa, run + stride);
+        __builtin_amdgcn_sched_barrier(0);
+        process(xb, run);
+        __builtin_amdgcn_sched_barrier(0);
+        run += stride;
+    }
+}
+
+bool thin_cols_applicable(const IgemmArgs &a)
+{
+    const bool dense = a.sh == 1 && a.sw == 1 && a.osh == 1 && a.osw == 1 && a.FH == a.OH && a.FW == a.OW &&
+                       a.IH == a.OH && a.IW == a.OW && a.ooh == 0 && a.oow == 0;
+    return dense && a.TR == 1 && a.TS == 1 && a.th0 == 0 && a.tw0 == 0 && a.Cin == TC_CIN && a.Nout >= 1 &&
+           a.Nout <= THIN_MAX && a.ldd == a.Nout && !a.resid && !a.b_transposed;
+}
+
+hipError_t launch_thin_cols(const IgemmArgs &a, bool is_bf16, hipStream_t stream)
+{
+    const int64_t M = (int64_t)a.NB * a.OH * a.OW;
+    if (M <= 0) return hipSuccess;
+    const int64_t runs = (M + TC_RUN - 1) / TC_RUN;
+    const int64_t want = (runs + 3) / 4;                  // one run per wavefront at least
+    const dim3 grid((unsigned)(want < 2048 ? want : 2048)), block(256);
+    const bool tail = a.bias || a.relu;
+    auto go = [&](auto kk, auto has_tail) {
+        constexpr int KK = decltype(kk)::value;
+        constexpr bool TAIL = decltype(has_tail)::value;
+        if (is_bf16) DLK_LAUNCH("thin_cols_kernel", (thin_cols_kernel<BF16, KK, TAIL>), grid, block, 0, stream, a);
+        else DLK_LAUNCH("thin_cols_kernel", (thin_cols_kernel<F16, KK, TAIL>), grid, block, 0, stream, a);
+    };
+    auto by_tail = [&](auto kk) {
+        if (tail) go(kk, std::true_type{});
+        else go(kk, std::false_type{});
+    };
+    switch (a.Nout) {
+        case 1: by_tail(std::integral_constant<int, 1>{}); break;
+        case 2: by_tail(std::integral_constant<int, 2>{}); break;
+        case 3: by_tail(std::integral_constant<int, 3>{}); break;
+        case 4: by_tail(std::integral_constant<int, 4>{}); break;
+        default: return hipErrorInvalidValue;
+    }
+    return dlk::launch_status();
+}
+
 // Filter gradient of a 1x1, stride-1, unpadded convolution with K <= THIN_MAX:
 //   partial[b][k][c] = sum over workgroup b's pixels of dy[pix][k] * x[pix][c].
 // A workgroup is (C/8 channel groups) x (256 / (C/8) pixel lanes); every thread

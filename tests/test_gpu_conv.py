@@ -113,6 +113,11 @@ SMALL = [
     L("1x1.k48", 1, 20, 30, 256, 48, 1, 1, 1, 0, 1),
     L("1x1.k4.c304", 2, 21, 30, 304, 4, 1, 1, 1, 0, 1),
     L("1x1.k2.c8", 1, 9, 10, 8, 2, 1, 1, 1, 0, 1),
+    # 256 input channels and 1..4 output channels: the streaming forward kernel (runs of 16 pixels per wavefront)
+    L("1x1.c256.k1.one-pixel", 1, 1, 1, 256, 1, 1, 1, 1, 0, 1),
+    L("1x1.c256.k2.ragged-run", 1, 5, 7, 256, 2, 1, 1, 1, 0, 1),
+    L("1x1.c256.k4", 2, 9, 7, 256, 4, 1, 1, 1, 0, 1),
+    L("1x1.c256.k3.many-runs", 1, 301, 171, 256, 3, 1, 1, 1, 0, 1),            # more runs than wavefronts in the grid
     L("3x3.c304", 1, 12, 40, 304, 256, 3, 3, 1, 1, 1),
     L("3x3.d6.small-map", 2, 10, 14, 64, 32, 3, 3, 1, 6, 6),
     L("3x3.d12.small-map", 1, 12, 18, 32, 64, 3, 3, 1, 12, 12),

@@ -152,6 +152,7 @@ RESIDUAL_CASES = [
     (L("r.halo.d2.k192", 1, 230, 250, 32, 192, 3, 3, 1, 2, 2), "bf16"),
     (L("r.scalar.odd-channels", 2, 9, 11, 3, 5, 3, 3, 1, 1, 1), "f16"),
     (L("r.thin.c4", 1, 40, 50, 4, 64, 1, 1, 1, 0, 1), "bf16"),
+    (L("r.logits.k3", 1, 33, 47, 256, 3, 1, 1, 1, 0, 1), "f16"),                      # would take the streaming forward kernel
     (L("r.would-be-halo3x3.k256", 1, 200, 230, 40, 256, 3, 3, 1, 1, 1), "f16"),
     (L("r.would-be-narrow5x5.k32", 4, 75, 200, 16, 32, 5, 5, 1, 2, 1), "f16"),
     (L("r.would-be-wide5x5.c32.k80", 3, 100, 230, 32, 80, 5, 5, 1, 2, 1), "bf16"),
