@@ -170,6 +170,7 @@ def test_describe_names_the_kernels_of_the_decoder_layers(api):
     stem = api.ConvDesc(2, 768, 1152, 16, 64, 7, 7, 2, 2, 3, 3, 1, 1, api.DL_F16)
     assert "dgrad_stem_kernel" in api.dl_conv_describe(stem, api.PASS_BWD_DATA)
     logits = api.ConvDesc(2, 768, 1152, 256, 3, 1, 1, 1, 1, 0, 0, 1, 1, api.DL_F16)
+    assert api.dl_conv_describe(logits, api.PASS_FWD) == "thin_cols_kernel[2048]"
     assert "thin_rows_kernel" in api.dl_conv_describe(logits, api.PASS_BWD_DATA)
     assert "thin_wgrad_kernel" in api.dl_conv_describe(logits, api.PASS_BWD_FILTER)
     # the query leaves nothing behind: a call after it still validates and reports as before
